@@ -1,0 +1,214 @@
+/*
+ * srq.h - C ABI of the sparse-residual-compensated quantized GEMM for MI355X (gfx950).
+ *
+ * The library computes  D = alpha * (A.B, quantized and compensated) + beta * C  following
+ * Algorithm 1 of Gu et al., "A method for accelerating low precision operations by sparse
+ * matrix multiplication":  vector-wise symmetric quantization of A (one scale per row) and
+ * B (one scale per column) (Sec. 3.2), an INT8 x INT8 -> INT32 product, dequantization by
+ * the outer product of the scales (Eq. "quantized GEMM"), and a correction built from the
+ * quantized residual matrices (Sec. 2.3, Eq. gemm_r) in which the operands are first
+ * reduced to sparse matrices by the threshold rule of Eq. avgQuan (Sec. 3.1.1).
+ *
+ * Conventions (all entry points)
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless a comment says
+ *     "host".  Matrices are row-major with an explicit leading dimension counted in
+ *     elements.  The library never allocates or frees device memory; scratch space comes
+ *     from the workspace the caller attaches to the handle.
+ *   - `stream` is the caller's hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work and return without waiting, except where a comment says the
+ *     call synchronises.
+ *   - Every call returns an srq_status_t.  Arguments are validated before anything is
+ *     launched; a non-zero status means nothing was enqueued (except SRQ_STATUS_CAPACITY,
+ *     see srq_compensated_gemm).
+ *   - qmax = 2^(bits-1) - 1 (Sec. 2.3, lambda = (2^(N-1)-1)/a_max); bits in 2..8, codes are
+ *     always stored in int8 containers.  K * qmax^2 must stay below 2^31 so the INT32
+ *     accumulators cannot overflow.
+ *   - "Vector" means a quantization vector: a row for SRQ_AXIS_ROW, a column for
+ *     SRQ_AXIS_COL.  Code matrices are stored either vector-major (code of element e of
+ *     vector v at Q[v*ld + e]) or element-major (Q[e*ld + v]).  For SRQ_AXIS_ROW
+ *     vector-major is the layout of X itself; for SRQ_AXIS_COL element-major is.
+ *   - Inputs must be finite; a vector whose maximum magnitude is zero gets scale 0,
+ *     lambda 0 and all-zero codes.
+ */
+#ifndef SRQ_H_
+#define SRQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum srq_status_t {
+  SRQ_STATUS_OK = 0,
+  SRQ_STATUS_INVALID_ARG = 1,   /* null pointer, negative size, ld too small, bad enum     */
+  SRQ_STATUS_UNSUPPORTED = 2,   /* bits outside 2..8                                        */
+  SRQ_STATUS_K_OVERFLOW = 3,    /* K * qmax^2 >= 2^31                                       */
+  SRQ_STATUS_CAPACITY = 4,      /* compressed-storage capacity too small for the selection  */
+  SRQ_STATUS_WORKSPACE = 5,     /* no workspace attached, or too small                      */
+  SRQ_STATUS_HIP_ERROR = 6,     /* a HIP runtime call failed (see srq_last_hip_error)       */
+  SRQ_STATUS_NO_DEVICE = 7      /* arguments are valid but the handle has no device         */
+} srq_status_t;
+
+typedef enum srq_axis_t { SRQ_AXIS_ROW = 0, SRQ_AXIS_COL = 1 } srq_axis_t;
+typedef enum srq_layout_t { SRQ_LAYOUT_VECTOR_MAJOR = 0, SRQ_LAYOUT_ELEMENT_MAJOR = 1 } srq_layout_t;
+
+/* Rounding of lambda*x to an integer (Eq. Quantization's TypeCast).  The paper's worked
+ * examples truncate; nearest-even is the default used for every measured workload. */
+typedef enum srq_round_t { SRQ_ROUND_NEAREST_EVEN = 0, SRQ_ROUND_TRUNC = 1 } srq_round_t;
+
+/* How the sparse products of Algorithm 1's SPMM line are executed.  Every strategy returns
+ * the same INT32 values. */
+typedef enum srq_strategy_t {
+  SRQ_STRATEGY_AUTO = 0,        /* pick per term from the measured density (synchronises)   */
+  SRQ_STRATEGY_CSR_VALU = 1,    /* row-wise CSR x dense on the vector ALUs                   */
+  SRQ_STRATEGY_CSR_MFMA = 2     /* CSR expanded to zero-filled INT8 tiles, matrix cores      */
+} srq_strategy_t;
+
+typedef struct srq_context* srq_handle_t;
+
+/* Statistics written to device memory by srq_compensated_gemm. */
+typedef struct srq_stats_t {
+  int64_t nnz_a;        /* entries kept in A' (Algorithm 1, getSparsity)                    */
+  int64_t nnz_b;        /* entries kept in B'                                               */
+  int32_t path_a;       /* 0 = term skipped (theta = inf), 1 = CSR_VALU, 2 = CSR_MFMA,      */
+  int32_t path_b;       /* 3 = dense branch on the unreduced operand                        */
+} srq_stats_t;
+
+/* Optional extra outputs of srq_compensated_gemm for stage-by-stage checks; any member may
+ * be NULL.  Each is a caller-owned device buffer of M*N elements, row-major, ld = N. */
+typedef struct srq_debug_t {
+  int32_t* D_int;       /* A_int . B_int                                                    */
+  float*   D_F;         /* its dequantization, before any correction                        */
+  int32_t* DR1_int;     /* A'_int . RB_int   (or A_int . RB_int on the dense branch)        */
+  int32_t* DR2_int;     /* RA_int . B'_int   (or RA_int . B_int on the dense branch)        */
+} srq_debug_t;
+
+/* Device pointers INTO THE WORKSPACE to the intermediates of the last
+ * srq_compensated_gemm call on this handle (valid until the next call or until the
+ * workspace is replaced).  Code matrices: A-side M x K vector-major (ld = K); B-side
+ * N x K vector-major (ld = K).  Element-major residual codes: RB_em is K x N (ld = N),
+ * RA_em is K x M (ld = M); they are only filled when a term ran as CSR_VALU. */
+typedef struct srq_intermediates_t {
+  const int8_t *A_int, *B_int, *RA_int, *RB_int, *RA_em, *RB_em;
+  const float *s_a, *lam_a, *s_ra, *s_b, *lam_b, *s_rb;   /* [M] resp. [N]                 */
+  const float *drow, *dcol, *t_a, *t_b;                   /* [M] resp. [N]                 */
+  const int32_t *a_ptr, *a_idx; const int8_t* a_val;      /* CSR of A'_int                  */
+  const int32_t *b_ptr, *b_idx; const int8_t* b_val;      /* CSC of B'_int                  */
+  int64_t capacity_a, capacity_b;                         /* entries that fit idx/val       */
+} srq_intermediates_t;
+
+/* ---- lifecycle -------------------------------------------------------------------- */
+
+/* Creates a handle bound to HIP device `device` (host call).  device = -1 creates a handle
+ * without a device: every entry point still validates its arguments and then returns
+ * SRQ_STATUS_NO_DEVICE instead of launching (used to test validation on a CPU-only host). */
+srq_status_t srq_create(srq_handle_t* handle, int device);
+srq_status_t srq_destroy(srq_handle_t handle);
+
+/* Bytes of workspace srq_compensated_gemm needs for an M x N x K problem when at most
+ * `max_density` (0..1] of each operand's entries are kept.  Host call, no device needed. */
+srq_status_t srq_workspace_bytes(int64_t M, int64_t N, int64_t K, double max_density, size_t* bytes);
+
+/* Attaches caller-owned device memory (256-byte aligned) as the handle's workspace.  The
+ * staged entry points below need at least srq_stage_workspace_bytes(M, N, K) bytes of it
+ * for operands of an M x N x K problem (a workspace sized by srq_workspace_bytes for the
+ * same problem is always enough). */
+srq_status_t srq_set_workspace(srq_handle_t handle, void* workspace, size_t bytes);
+srq_status_t srq_stage_workspace_bytes(int64_t M, int64_t N, int64_t K, size_t* bytes);
+
+/* Last hipError_t seen by this handle as an int (0 = hipSuccess).  Host call. */
+int srq_last_hip_error(srq_handle_t handle);
+const char* srq_status_string(srq_status_t status);
+
+/* ---- quantize: Algorithm 1 line 1 (Eq. Quantization, Eq. getlambda, Sec. 3.2) -------- */
+
+/* For every vector v of X[rows x cols] (ldx >= cols):  amax = max|x|, lambda_v =
+ * fl(qmax/amax), scale_v = fl(amax/qmax), code = clamp(round(fl(x*lambda_v)), -qmax, qmax).
+ *   Q      out, int8, rows*cols codes in `layout` (ldq >= vector length for vector-major,
+ *          >= number of vectors for element-major)
+ *   scale  out, float[number of vectors]   (the dequantization factor 1/lambda)
+ *   lambda out, float[number of vectors], may be NULL
+ * rows or cols equal to 0 is a valid no-op. */
+srq_status_t srq_quantize(srq_handle_t handle, const float* X, int64_t rows, int64_t cols, int64_t ldx,
+                          srq_axis_t axis, int bits, srq_round_t round, srq_layout_t layout,
+                          int8_t* Q, int64_t ldq, float* scale, float* lambda, void* stream);
+
+/* ---- build_sparse_residual: Algorithm 1 lines 4-10 for one operand -------------------- */
+
+/* Given X, its vector scales/lambdas (from srq_quantize) and a threshold per vector
+ * (thresh_v = theta * mean|D_F| over the vector's row resp. column of D_F, Eq. avgQuan):
+ *   1. residual r = fl(x - fl(float(code)*scale_v)) with code recomputed from X and lambda
+ *      (Sec. 2.3), quantized again per vector -> Rq (layout `r_layout`, ld `ldr`), rscale;
+ *   2. the reduced operand: entry kept iff |x| > thresh_v (strict); kept codes compacted
+ *      vector by vector, ascending element index: ptr[int32, nvec+1], idx[int32], val[int8]
+ *      (CSR of A' for SRQ_AXIS_ROW, CSC of B' for SRQ_AXIS_COL).  Kept entries whose code
+ *      is 0 are stored.
+ * `capacity` = entries idx/val can hold.  nnz_dev (device int64) receives the number of
+ * kept entries; if it exceeds `capacity` only ptr is complete and idx/val hold the first
+ * `capacity` entries - the caller checks after synchronising.  Rq/rscale may both be NULL
+ * to skip step 1; ptr/idx/val may all be NULL to skip step 2. */
+srq_status_t srq_build_sparse_residual(srq_handle_t handle, const float* X, int64_t rows, int64_t cols,
+                                       int64_t ldx, srq_axis_t axis, const float* scale,
+                                       const float* lambda, const float* thresh, int bits,
+                                       srq_round_t round, int8_t* Rq, int64_t ldr, srq_layout_t r_layout,
+                                       float* rscale, int32_t* ptr, int32_t* idx, int8_t* val,
+                                       int64_t capacity, int64_t* nnz_dev, void* stream);
+
+/* ---- staged products (Algorithm 1 lines 2-3, 7, 12, 16-17), used by parity tests and by
+ *      callers that keep operands quantized ------------------------------------------------ */
+
+/* D_int[i,j] = sum_k Qa[i*lda+k] * Qb[j*ldb+k]  (both operands vector-major, K contiguous);
+ * D_F[i,j] = fl(fl(float(D_int)) * fl(sa[i]*sb[j])).  D_int (ld = ldd) may be NULL.
+ * drow[M], dcol[N] receive the means of |D_F| over each row / column (Sec. 3.1.1), summed
+ * in double in a fixed order; both may be NULL. */
+srq_status_t srq_gemm_i8(srq_handle_t handle, int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
+                         const float* sa, const int8_t* Qb, int64_t ldb, const float* sb, float* D_F,
+                         int32_t* D_int, int64_t ldd, float* drow, float* dcol, void* stream);
+
+/* C[i,j] += fl(fl(float(DR[i,j])) * fl(s_row[i]*s_col[j])) with DR the product of a
+ * compressed operand and dense residual codes:
+ *   side = SRQ_AXIS_ROW: DR = A'.RB, (ptr,idx,val) = CSR of A' (M vectors over K), Rq = RB codes;
+ *   side = SRQ_AXIS_COL: DR = RA.B', (ptr,idx,val) = CSC of B' (N vectors over K), Rq = RA codes.
+ * Rq layout: CSR_VALU wants the residual codes k-major (RB element-major K x N, ld >= N;
+ * RA element-major K x M, ld >= M); CSR_MFMA wants them K-contiguous (RB vector-major
+ * N x K; RA vector-major M x K; ld >= K).  SRQ_STRATEGY_AUTO is not accepted here.
+ * s_row[M] / s_col[N] are the scales paired with rows / columns of C for this term.
+ * DR_int (ld = ldc) may be NULL. */
+srq_status_t srq_spmm_accumulate(srq_handle_t handle, srq_axis_t side, srq_strategy_t strategy, int64_t M,
+                                 int64_t N, int64_t K, const int32_t* ptr, const int32_t* idx,
+                                 const int8_t* val, const int8_t* Rq, int64_t ldr, const float* s_row,
+                                 const float* s_col, float* C, int32_t* DR_int, int64_t ldc, void* stream);
+
+/* ---- compensated_gemm: the whole of Algorithm 1 ---------------------------------------- */
+
+/* C[M x N] = alpha * ( D_F + dequant(DR1_int) + dequant(DR2_int) ) + beta * Cin.
+ *   A [M x K] (lda >= K), B [K x N] (ldb >= N), C (ldc >= N): float, row-major.
+ *   theta_a, theta_b   threshold factor of Eq. avgQuan for A resp. B (the paper has one
+ *                      theta: pass it twice).  +inf keeps nothing: plain vector-wise
+ *                      quantized GEMM.  0 keeps every non-zero entry: dense compensation.
+ *   dense_fallback_density   Algorithm 1's limit "s": a term whose reduced operand has
+ *                      density >= s runs as a dense product on the UNREDUCED codes.  Values
+ *                      > 1 switch the branch off.  Any value <= 1 makes the call synchronise
+ *                      once on `stream` to read the densities, as SRQ_STRATEGY_AUTO does.
+ *   Cin                read only if beta != 0 (ldcin >= N); must not overlap C.
+ *   stats_dev          device srq_stats_t, may be NULL.
+ *   dbg                host pointer to a struct of device buffers, may be NULL.
+ * Returns SRQ_STATUS_CAPACITY (after the selection ran, C not written) when a synchronising
+ * mode finds more kept entries than the workspace was sized for; in non-synchronising
+ * modes the compressed arrays are truncated instead and stats_dev tells. */
+srq_status_t srq_compensated_gemm(srq_handle_t handle, int64_t M, int64_t N, int64_t K, const float* A,
+                                  int64_t lda, const float* B, int64_t ldb, float theta_a, float theta_b,
+                                  int bits, srq_round_t round, float dense_fallback_density,
+                                  srq_strategy_t strategy, float alpha, float beta, const float* Cin,
+                                  int64_t ldcin, float* C, int64_t ldc, srq_stats_t* stats_dev,
+                                  const srq_debug_t* dbg, void* stream);
+
+/* Fills `out` (host struct) with workspace pointers to the last call's intermediates. */
+srq_status_t srq_get_intermediates(srq_handle_t handle, srq_intermediates_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SRQ_H_ */

@@ -1,0 +1,567 @@
+// Host side of the C ABI: argument validation, workspace planning and the kernel pipeline of
+// Algorithm 1.  No device memory is allocated here; everything lives in the caller's
+// workspace.
+#include <math.h>
+#include <new>
+#include <string.h>
+
+#include "srq_internal.h"
+
+using namespace srq;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// density at and above which the matrix-core execution of the sparse products is chosen
+// by SRQ_STRATEGY_AUTO (measured crossover of the two kernels on MI355X)
+constexpr double kAutoMfmaDensity = 0.02;
+
+struct Carver {
+  char* base;
+  size_t off;
+  template <class T>
+  T* take(size_t n) {
+    T* p = reinterpret_cast<T*>(base + off);
+    off += align_up(n * sizeof(T));
+    return p;
+  }
+};
+
+struct Plan {
+  int8_t *A_int, *B_int, *RA_int, *RB_int, *RA_em, *RB_em, *Ad, *Bd;
+  float *s_a, *lam_a, *s_ra, *lam_ra, *drow, *t_a;
+  float *s_b, *lam_b, *s_rb, *lam_rb, *dcol, *t_b;
+  double *row_part, *col_part;
+  int32_t *cnt_a, *tot_a, *a_ptr, *cnt_b, *tot_b, *b_ptr;
+  int64_t* nnz;   // [2]
+  int32_t *a_idx, *b_idx;
+  int8_t *a_val, *b_val;
+  int64_t cap_a, cap_b;
+  size_t fixed_bytes;
+};
+
+int64_t tiles(int64_t n, int t) { return (n + t - 1) / t; }
+
+// Lays the fixed-size regions out; returns the bytes they take.  base may be null (sizing).
+size_t plan_fixed(char* base, int64_t M, int64_t N, int64_t K, Plan* p) {
+  Carver c{base, 0};
+  size_t mk = (size_t)M * K, nk = (size_t)N * K;
+  p->A_int = c.take<int8_t>(mk);
+  p->B_int = c.take<int8_t>(nk);
+  p->RA_int = c.take<int8_t>(mk);
+  p->RB_int = c.take<int8_t>(nk);
+  p->RA_em = c.take<int8_t>(mk);
+  p->RB_em = c.take<int8_t>(nk);
+  p->Ad = c.take<int8_t>(mk);
+  p->Bd = c.take<int8_t>(nk);
+  p->s_a = c.take<float>(M); p->lam_a = c.take<float>(M); p->s_ra = c.take<float>(M);
+  p->lam_ra = c.take<float>(M); p->drow = c.take<float>(M); p->t_a = c.take<float>(M);
+  p->s_b = c.take<float>(N); p->lam_b = c.take<float>(N); p->s_rb = c.take<float>(N);
+  p->lam_rb = c.take<float>(N); p->dcol = c.take<float>(N); p->t_b = c.take<float>(N);
+  p->row_part = c.take<double>((size_t)tiles(N, gemm_tile_n()) * M);
+  p->col_part = c.take<double>((size_t)tiles(M, gemm_tile_m()) * N);
+  int64_t chk = select_chunks(K);
+  p->cnt_a = c.take<int32_t>((size_t)chk * M); p->tot_a = c.take<int32_t>(M);
+  p->a_ptr = c.take<int32_t>(M + 1);
+  p->cnt_b = c.take<int32_t>((size_t)chk * N); p->tot_b = c.take<int32_t>(N);
+  p->b_ptr = c.take<int32_t>(N + 1);
+  p->nnz = c.take<int64_t>(2);
+  p->fixed_bytes = c.off;
+  return c.off;
+}
+
+// Splits what is left of the workspace into the two compressed operands.
+bool plan_compressed(char* base, size_t bytes, int64_t M, int64_t N, int64_t K, Plan* p) {
+  if (bytes < p->fixed_bytes + 4 * kAlign) { p->cap_a = p->cap_b = 0; return false; }
+  size_t rest = bytes - p->fixed_bytes - 4 * kAlign;
+  double total = (double)(rest / 5);
+  double fa = (M + N) > 0 ? (double)M / (double)(M + N) : 0.5;
+  int64_t cap_a = (int64_t)(total * fa), cap_b = (int64_t)(total * (1.0 - fa));
+  int64_t max_a = M * K, max_b = N * K;
+  if (cap_a > max_a) cap_a = max_a;
+  if (cap_b > max_b) cap_b = max_b;
+  const int64_t lim = 2147483647;
+  if (cap_a > lim) cap_a = lim;
+  if (cap_b > lim) cap_b = lim;
+  p->cap_a = cap_a;
+  p->cap_b = cap_b;
+  if (base) {
+    Carver c{base, p->fixed_bytes};
+    p->a_idx = c.take<int32_t>(cap_a);
+    p->a_val = c.take<int8_t>(cap_a);
+    p->b_idx = c.take<int32_t>(cap_b);
+    p->b_val = c.take<int8_t>(cap_b);
+  }
+  return true;
+}
+
+size_t stage_bytes(int64_t M, int64_t N, int64_t K) {
+  size_t big = (size_t)(M > N ? M : N);
+  size_t mx = big > (size_t)K ? big : (size_t)K;
+  size_t b = 0;
+  b += align_up(mx * 4) * 4;                                            // lambdas, totals, ptr
+  b += align_up(((size_t)select_chunks(K) * big + (size_t)select_chunks(big) * K) * 4);  // counts
+  b += align_up(((size_t)tiles(N, gemm_tile_n()) * M + (size_t)tiles(M, gemm_tile_m()) * N) * 8);
+  b += align_up(big * K);                                               // expanded operand
+  return b + 8 * kAlign;
+}
+
+inline srq_status_t hip_fail(srq_handle_t h, hipError_t e) {
+  if (h) h->last_hip_error = (int)e;
+  return SRQ_STATUS_HIP_ERROR;
+}
+
+#define SRQ_HIP(h, expr)                                   \
+  do {                                                     \
+    hipError_t e__ = (expr);                               \
+    if (e__ != hipSuccess) return hip_fail((h), e__);      \
+  } while (0)
+
+srq_status_t check_common(srq_handle_t h, int bits) {
+  if (!h) return SRQ_STATUS_INVALID_ARG;
+  if (bits < 2 || bits > 8) return SRQ_STATUS_UNSUPPORTED;
+  return SRQ_STATUS_OK;
+}
+
+bool k_overflows(int64_t K, int qmax) { return K * (int64_t)qmax * qmax >= (1LL << 31); }
+
+srq_status_t bind_device(srq_handle_t h) {
+  if (h->device < 0) return SRQ_STATUS_NO_DEVICE;
+  SRQ_HIP(h, hipSetDevice(h->device));
+  return SRQ_STATUS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* srq_status_string(srq_status_t s) {
+  switch (s) {
+    case SRQ_STATUS_OK: return "ok";
+    case SRQ_STATUS_INVALID_ARG: return "invalid argument";
+    case SRQ_STATUS_UNSUPPORTED: return "unsupported bit width";
+    case SRQ_STATUS_K_OVERFLOW: return "K*qmax^2 overflows the INT32 accumulator";
+    case SRQ_STATUS_CAPACITY: return "compressed-storage capacity too small";
+    case SRQ_STATUS_WORKSPACE: return "workspace missing or too small";
+    case SRQ_STATUS_HIP_ERROR: return "HIP runtime error";
+    case SRQ_STATUS_NO_DEVICE: return "handle has no device";
+  }
+  return "unknown status";
+}
+
+srq_status_t srq_create(srq_handle_t* handle, int device) {
+  if (!handle) return SRQ_STATUS_INVALID_ARG;
+  *handle = nullptr;
+  srq_context* c = new (std::nothrow) srq_context();
+  if (!c) return SRQ_STATUS_INVALID_ARG;
+  memset(c, 0, sizeof(*c));
+  c->device = device;
+  if (device >= 0) {
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess || device >= n) { delete c; return SRQ_STATUS_HIP_ERROR; }
+    e = hipSetDevice(device);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->host_nnz), 2 * sizeof(int64_t), 0);
+    if (e != hipSuccess) { delete c; return SRQ_STATUS_HIP_ERROR; }
+  }
+  *handle = c;
+  return SRQ_STATUS_OK;
+}
+
+srq_status_t srq_destroy(srq_handle_t h) {
+  if (!h) return SRQ_STATUS_INVALID_ARG;
+  if (h->host_nnz) (void)hipHostFree(h->host_nnz);
+  delete h;
+  return SRQ_STATUS_OK;
+}
+
+int srq_last_hip_error(srq_handle_t h) { return h ? h->last_hip_error : 0; }
+
+srq_status_t srq_workspace_bytes(int64_t M, int64_t N, int64_t K, double max_density, size_t* bytes) {
+  if (!bytes || M < 0 || N < 0 || K < 0 || !(max_density >= 0.0) || max_density > 1.0)
+    return SRQ_STATUS_INVALID_ARG;
+  Plan p;
+  size_t fixed = plan_fixed(nullptr, M, N, K, &p);
+  // the capacity is shared out in proportion to the operand sizes, so size for the larger
+  double entries = max_density * (double)K * (double)(M + N) + 1024.0;
+  size_t total = fixed + 4 * kAlign + (size_t)(entries * 5.0) + 64;
+  size_t st = stage_bytes(M, N, K);
+  *bytes = align_up(total > st ? total : st);
+  return SRQ_STATUS_OK;
+}
+
+srq_status_t srq_stage_workspace_bytes(int64_t M, int64_t N, int64_t K, size_t* bytes) {
+  if (!bytes || M < 0 || N < 0 || K < 0) return SRQ_STATUS_INVALID_ARG;
+  *bytes = stage_bytes(M, N, K);
+  return SRQ_STATUS_OK;
+}
+
+srq_status_t srq_set_workspace(srq_handle_t h, void* ws, size_t bytes) {
+  if (!h) return SRQ_STATUS_INVALID_ARG;
+  if (ws && (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return SRQ_STATUS_INVALID_ARG;
+  h->ws = ws;
+  h->ws_bytes = ws ? bytes : 0;
+  memset(&h->last, 0, sizeof(h->last));
+  return SRQ_STATUS_OK;
+}
+
+srq_status_t srq_get_intermediates(srq_handle_t h, srq_intermediates_t* out) {
+  if (!h || !out) return SRQ_STATUS_INVALID_ARG;
+  *out = h->last;
+  return SRQ_STATUS_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+srq_status_t srq_quantize(srq_handle_t h, const float* X, int64_t rows, int64_t cols, int64_t ldx,
+                          srq_axis_t axis, int bits, srq_round_t round, srq_layout_t layout,
+                          int8_t* Q, int64_t ldq, float* scale, float* lambda, void* stream) {
+  srq_status_t s = check_common(h, bits);
+  if (s) return s;
+  if (rows < 0 || cols < 0) return SRQ_STATUS_INVALID_ARG;
+  if (axis != SRQ_AXIS_ROW && axis != SRQ_AXIS_COL) return SRQ_STATUS_INVALID_ARG;
+  if (round != SRQ_ROUND_NEAREST_EVEN && round != SRQ_ROUND_TRUNC) return SRQ_STATUS_INVALID_ARG;
+  if (layout != SRQ_LAYOUT_VECTOR_MAJOR && layout != SRQ_LAYOUT_ELEMENT_MAJOR) return SRQ_STATUS_INVALID_ARG;
+  int64_t nvec = axis == SRQ_AXIS_ROW ? rows : cols, veclen = axis == SRQ_AXIS_ROW ? cols : rows;
+  if (rows == 0 || cols == 0) {
+    // no codes; scales of empty vectors are zero, nothing to validate beyond the handle
+    if (nvec > 0 && !scale) return SRQ_STATUS_INVALID_ARG;
+  } else {
+    if (!X || !Q || !scale) return SRQ_STATUS_INVALID_ARG;
+    if (ldx < cols) return SRQ_STATUS_INVALID_ARG;
+    if (ldq < (layout == SRQ_LAYOUT_VECTOR_MAJOR ? veclen : nvec)) return SRQ_STATUS_INVALID_ARG;
+  }
+  float* lam = lambda;
+  if (!lam && rows > 0 && cols > 0) {
+    if (!h->ws || h->ws_bytes < align_up((size_t)nvec * 4)) return SRQ_STATUS_WORKSPACE;
+    lam = reinterpret_cast<float*>(h->ws);
+  }
+  s = bind_device(h);
+  if (s) return s;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  int qmax = qmax_of_bits(bits);
+  if (nvec == 0) return SRQ_STATUS_OK;
+  SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(scale), nvec, 0, st));
+  if (rows == 0 || cols == 0) {
+    if (lambda) SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(lambda), nvec, 0, st));
+    return SRQ_STATUS_OK;
+  }
+  SRQ_HIP(h, launch_amax(X, rows, cols, ldx, axis, reinterpret_cast<uint32_t*>(scale), st));
+  SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(scale), lam, nvec, qmax, st));
+  SRQ_HIP(h, launch_quantize_tiles(X, rows, cols, ldx, axis, scale, lam, qmax, round == SRQ_ROUND_TRUNC,
+                                   layout, Q, ldq, nullptr, st));
+  return SRQ_STATUS_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+srq_status_t srq_build_sparse_residual(srq_handle_t h, const float* X, int64_t rows, int64_t cols,
+                                       int64_t ldx, srq_axis_t axis, const float* scale,
+                                       const float* lambda, const float* thresh, int bits,
+                                       srq_round_t round, int8_t* Rq, int64_t ldr, srq_layout_t r_layout,
+                                       float* rscale, int32_t* ptr, int32_t* idx, int8_t* val,
+                                       int64_t capacity, int64_t* nnz_dev, void* stream) {
+  srq_status_t s = check_common(h, bits);
+  if (s) return s;
+  if (rows < 0 || cols < 0) return SRQ_STATUS_INVALID_ARG;
+  if (axis != SRQ_AXIS_ROW && axis != SRQ_AXIS_COL) return SRQ_STATUS_INVALID_ARG;
+  if (round != SRQ_ROUND_NEAREST_EVEN && round != SRQ_ROUND_TRUNC) return SRQ_STATUS_INVALID_ARG;
+  if (r_layout != SRQ_LAYOUT_VECTOR_MAJOR && r_layout != SRQ_LAYOUT_ELEMENT_MAJOR) return SRQ_STATUS_INVALID_ARG;
+  const bool do_res = Rq || rscale, do_sel = ptr || idx || val;
+  if (do_res && (!Rq || !rscale)) return SRQ_STATUS_INVALID_ARG;
+  if (do_sel && (!ptr || !thresh || capacity < 0 || (capacity > 0 && (!idx || !val)))) return SRQ_STATUS_INVALID_ARG;
+  if (capacity > 2147483647LL) return SRQ_STATUS_INVALID_ARG;
+  int64_t nvec = axis == SRQ_AXIS_ROW ? rows : cols, veclen = axis == SRQ_AXIS_ROW ? cols : rows;
+  if (rows > 0 && cols > 0) {
+    if (!X || !scale || !lambda) return SRQ_STATUS_INVALID_ARG;
+    if (ldx < cols) return SRQ_STATUS_INVALID_ARG;
+    if (do_res && ldr < (r_layout == SRQ_LAYOUT_VECTOR_MAJOR ? veclen : nvec)) return SRQ_STATUS_INVALID_ARG;
+  }
+  int64_t nch = select_chunks(veclen);
+  size_t need = align_up((size_t)nvec * 4) * 2 + align_up((size_t)nch * nvec * 4) + kAlign;
+  if (nvec > 0 && (!h->ws || h->ws_bytes < need)) return SRQ_STATUS_WORKSPACE;
+  s = bind_device(h);
+  if (s) return s;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  int qmax = qmax_of_bits(bits), trunc = round == SRQ_ROUND_TRUNC;
+  Carver c{reinterpret_cast<char*>(h->ws), 0};
+  float* rlam = c.take<float>(nvec);
+  int32_t* totals = c.take<int32_t>(nvec);
+  int32_t* cnt = c.take<int32_t>((size_t)nch * nvec);
+  if (do_res && nvec > 0) {
+    SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(rscale), nvec, 0, st));
+    SRQ_HIP(h, launch_quantize_tiles(X, rows, cols, ldx, axis, scale, lambda, qmax, trunc,
+                                     SRQ_LAYOUT_VECTOR_MAJOR, nullptr, 0,
+                                     reinterpret_cast<uint32_t*>(rscale), st));
+    SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(rscale), rlam, nvec, qmax, st));
+    bool vm = r_layout == SRQ_LAYOUT_VECTOR_MAJOR;
+    SRQ_HIP(h, launch_residual_tiles(X, rows, cols, ldx, axis, scale, lambda, rlam, qmax, trunc,
+                                     vm ? Rq : nullptr, ldr, vm ? nullptr : Rq, ldr, st));
+  }
+  if (do_sel) {
+    SRQ_HIP(h, launch_select_count(X, rows, cols, ldx, axis, thresh, cnt, st));
+    SRQ_HIP(h, launch_select_scan(cnt, nvec, (rows > 0 && cols > 0) ? nch : 0, totals, ptr, nnz_dev, st));
+    SRQ_HIP(h, launch_select_scatter(X, rows, cols, ldx, axis, thresh, lambda, qmax, trunc, ptr, cnt, idx,
+                                     val, capacity, st));
+  }
+  return SRQ_STATUS_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+srq_status_t srq_gemm_i8(srq_handle_t h, int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
+                         const float* sa, const int8_t* Qb, int64_t ldb, const float* sb, float* D_F,
+                         int32_t* D_int, int64_t ldd, float* drow, float* dcol, void* stream) {
+  if (!h) return SRQ_STATUS_INVALID_ARG;
+  if (M < 0 || N < 0 || K < 0) return SRQ_STATUS_INVALID_ARG;
+  if (k_overflows(K, 128)) return SRQ_STATUS_K_OVERFLOW;     // codes may use the full int8 range
+  if (M > 0 && N > 0) {
+    if (!sa || !sb || !D_F || ldd < N) return SRQ_STATUS_INVALID_ARG;
+    if (K > 0 && (!Qa || !Qb || lda < K || ldb < K)) return SRQ_STATUS_INVALID_ARG;
+  }
+  if ((drow == nullptr) != (dcol == nullptr)) return SRQ_STATUS_INVALID_ARG;
+  size_t need = align_up((size_t)tiles(N, gemm_tile_n()) * M * 8) + align_up((size_t)tiles(M, gemm_tile_m()) * N * 8);
+  if (drow && M > 0 && N > 0 && (!h->ws || h->ws_bytes < need)) return SRQ_STATUS_WORKSPACE;
+  srq_status_t s = bind_device(h);
+  if (s) return s;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (M == 0 || N == 0) return SRQ_STATUS_OK;
+  GemmEpilogue ep;
+  memset(&ep, 0, sizeof(ep));
+  ep.mode = kGemmFirst;
+  ep.s_row = sa; ep.s_col = sb; ep.C = D_F; ep.ldc = ldd; ep.D_int = D_int; ep.ldd = ldd;
+  ep.alpha = 1.f;
+  if (drow) {
+    Carver c{reinterpret_cast<char*>(h->ws), 0};
+    ep.row_part = c.take<double>((size_t)tiles(N, gemm_tile_n()) * M);
+    ep.col_part = c.take<double>((size_t)tiles(M, gemm_tile_m()) * N);
+  }
+  SRQ_HIP(h, launch_gemm_i8(M, N, K, Qa, lda, Qb, ldb, ep, st));
+  if (drow) {
+    SRQ_HIP(h, launch_reduce_means(ep.row_part, tiles(N, gemm_tile_n()), M, N, 0.f, drow, nullptr, st));
+    SRQ_HIP(h, launch_reduce_means(ep.col_part, tiles(M, gemm_tile_m()), N, M, 0.f, dcol, nullptr, st));
+  }
+  return SRQ_STATUS_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+srq_status_t srq_spmm_accumulate(srq_handle_t h, srq_axis_t side, srq_strategy_t strategy, int64_t M,
+                                 int64_t N, int64_t K, const int32_t* ptr, const int32_t* idx,
+                                 const int8_t* val, const int8_t* Rq, int64_t ldr, const float* s_row,
+                                 const float* s_col, float* C, int32_t* DR_int, int64_t ldc, void* stream) {
+  if (!h) return SRQ_STATUS_INVALID_ARG;
+  if (M < 0 || N < 0 || K < 0) return SRQ_STATUS_INVALID_ARG;
+  if (side != SRQ_AXIS_ROW && side != SRQ_AXIS_COL) return SRQ_STATUS_INVALID_ARG;
+  if (strategy != SRQ_STRATEGY_CSR_VALU && strategy != SRQ_STRATEGY_CSR_MFMA) return SRQ_STATUS_INVALID_ARG;
+  if (k_overflows(K, 128)) return SRQ_STATUS_K_OVERFLOW;
+  int64_t nvec = side == SRQ_AXIS_ROW ? M : N, nelem = side == SRQ_AXIS_ROW ? N : M;
+  if (M > 0 && N > 0) {
+    if (!ptr || !s_row || !s_col || !C || ldc < N) return SRQ_STATUS_INVALID_ARG;
+    if (K > 0) {
+      if (!Rq) return SRQ_STATUS_INVALID_ARG;
+      if (ldr < (strategy == SRQ_STRATEGY_CSR_VALU ? nelem : K)) return SRQ_STATUS_INVALID_ARG;
+    }
+  }
+  size_t need = align_up((size_t)nvec * K) + kAlign;
+  if (strategy == SRQ_STRATEGY_CSR_MFMA && M > 0 && N > 0 && K > 0 && (!h->ws || h->ws_bytes < need))
+    return SRQ_STATUS_WORKSPACE;
+  srq_status_t s = bind_device(h);
+  if (s) return s;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (M == 0 || N == 0) return SRQ_STATUS_OK;
+  GemmEpilogue ep;
+  memset(&ep, 0, sizeof(ep));
+  ep.mode = kGemmAccum;
+  ep.s_row = s_row; ep.s_col = s_col; ep.C = C; ep.ldc = ldc; ep.D_int = DR_int; ep.ldd = ldc;
+  ep.alpha = 1.f;
+  const int64_t cap = 2147483647LL;
+  if (strategy == SRQ_STRATEGY_CSR_VALU) {
+    SRQ_HIP(h, launch_spmm_valu(side == SRQ_AXIS_ROW ? 0 : 1, nvec, nelem, ptr, idx, val, cap, Rq, ldr, ep, st));
+  } else {
+    int8_t* dense = reinterpret_cast<int8_t*>(h->ws);
+    int64_t ldd = (K + 15) / 16 * 16;
+    if ((size_t)nvec * ldd > h->ws_bytes) ldd = K;
+    SRQ_HIP(h, launch_densify(ptr, idx, val, nvec, K, cap, dense, ldd, st));
+    if (side == SRQ_AXIS_ROW)
+      SRQ_HIP(h, launch_gemm_i8(M, N, K, dense, ldd, Rq, ldr, ep, st));
+    else
+      SRQ_HIP(h, launch_gemm_i8(M, N, K, Rq, ldr, dense, ldd, ep, st));
+  }
+  return SRQ_STATUS_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t K, const float* A,
+                                  int64_t lda, const float* B, int64_t ldb, float theta_a, float theta_b,
+                                  int bits, srq_round_t round, float dense_fallback_density,
+                                  srq_strategy_t strategy, float alpha, float beta, const float* Cin,
+                                  int64_t ldcin, float* C, int64_t ldc, srq_stats_t* stats_dev,
+                                  const srq_debug_t* dbg, void* stream) {
+  srq_status_t s = check_common(h, bits);
+  if (s) return s;
+  if (M < 0 || N < 0 || K < 0) return SRQ_STATUS_INVALID_ARG;
+  if (round != SRQ_ROUND_NEAREST_EVEN && round != SRQ_ROUND_TRUNC) return SRQ_STATUS_INVALID_ARG;
+  if (strategy != SRQ_STRATEGY_AUTO && strategy != SRQ_STRATEGY_CSR_VALU && strategy != SRQ_STRATEGY_CSR_MFMA)
+    return SRQ_STATUS_INVALID_ARG;
+  if (isnan(theta_a) || isnan(theta_b) || theta_a < 0.f || theta_b < 0.f) return SRQ_STATUS_INVALID_ARG;
+  if (isnan(dense_fallback_density) || isnan(alpha) || isnan(beta)) return SRQ_STATUS_INVALID_ARG;
+  const int qmax = qmax_of_bits(bits);
+  if (k_overflows(K, qmax)) return SRQ_STATUS_K_OVERFLOW;
+  if (M > 0 && N > 0) {
+    if (!C || ldc < N) return SRQ_STATUS_INVALID_ARG;
+    if (beta != 0.f && (!Cin || ldcin < N)) return SRQ_STATUS_INVALID_ARG;
+    if (K > 0 && (!A || !B || lda < K || ldb < N)) return SRQ_STATUS_INVALID_ARG;
+  }
+  const bool term_a = !isinf(theta_a), term_b = !isinf(theta_b);
+  const bool comp = (term_a || term_b) && K > 0;
+  Plan p;
+  memset(&p, 0, sizeof(p));
+  plan_fixed(nullptr, M, N, K, &p);
+  if (M > 0 && N > 0) {
+    if (!h->ws || h->ws_bytes < p.fixed_bytes) return SRQ_STATUS_WORKSPACE;
+    if (comp && !plan_compressed(nullptr, h->ws_bytes, M, N, K, &p)) return SRQ_STATUS_WORKSPACE;
+  }
+  s = bind_device(h);
+  if (s) return s;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (M == 0 || N == 0) return SRQ_STATUS_OK;
+
+  char* base = reinterpret_cast<char*>(h->ws);
+  plan_fixed(base, M, N, K, &p);
+  if (comp) plan_compressed(base, h->ws_bytes, M, N, K, &p);
+  const int trunc = round == SRQ_ROUND_TRUNC;
+  const bool scale_needed = alpha != 1.f || beta != 0.f;
+
+  srq_intermediates_t& im = h->last;
+  memset(&im, 0, sizeof(im));
+  im.A_int = p.A_int; im.B_int = p.B_int; im.s_a = p.s_a; im.lam_a = p.lam_a; im.s_b = p.s_b; im.lam_b = p.lam_b;
+
+  // lines 1: Quant.  amax per vector -> scale, lambda -> codes (and max |residual| per vector)
+  SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_a), M, 0, st));
+  SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_b), N, 0, st));
+  if (comp) {
+    SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_ra), M, 0, st));
+    SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_rb), N, 0, st));
+  }
+  SRQ_HIP(h, launch_amax(A, M, K, lda, SRQ_AXIS_ROW, reinterpret_cast<uint32_t*>(p.s_a), st));
+  SRQ_HIP(h, launch_amax(B, K, N, ldb, SRQ_AXIS_COL, reinterpret_cast<uint32_t*>(p.s_b), st));
+  SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_a), p.lam_a, M, qmax, st));
+  SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_b), p.lam_b, N, qmax, st));
+  SRQ_HIP(h, launch_quantize_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, qmax, trunc,
+                                   SRQ_LAYOUT_VECTOR_MAJOR, p.A_int, K,
+                                   comp ? reinterpret_cast<uint32_t*>(p.s_ra) : nullptr, st));
+  SRQ_HIP(h, launch_quantize_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, qmax, trunc,
+                                   SRQ_LAYOUT_VECTOR_MAJOR, p.B_int, K,
+                                   comp ? reinterpret_cast<uint32_t*>(p.s_rb) : nullptr, st));
+  if (comp) {
+    SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_ra), p.lam_ra, M, qmax, st));
+    SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_rb), p.lam_rb, N, qmax, st));
+    im.s_ra = p.s_ra; im.s_rb = p.s_rb;
+  }
+
+  // lines 2-3: D_int = A_int.B_int, D_F = dequant; line 7: partial sums of |D_F|
+  GemmEpilogue ep;
+  memset(&ep, 0, sizeof(ep));
+  ep.mode = kGemmFirst;
+  ep.s_row = p.s_a; ep.s_col = p.s_b; ep.C = C; ep.ldc = ldc;
+  ep.alpha = alpha; ep.beta = beta; ep.Cin = Cin; ep.ldcin = ldcin;
+  ep.ldd = N;
+  if (dbg) { ep.D_int = dbg->D_int; ep.D_F_copy = dbg->D_F; }
+  if (comp) { ep.row_part = p.row_part; ep.col_part = p.col_part; }
+  ep.final_scale = !comp && scale_needed;
+  SRQ_HIP(h, launch_gemm_i8(M, N, K, p.A_int, K, p.B_int, K, ep, st));
+  int path_a = 0, path_b = 0;
+  if (comp) {
+    // line 7: GetAvgVec, and the thresholds of Eq. avgQuan
+    SRQ_HIP(h, launch_reduce_means(p.row_part, tiles(N, gemm_tile_n()), M, N, theta_a, p.drow, p.t_a, st));
+    SRQ_HIP(h, launch_reduce_means(p.col_part, tiles(M, gemm_tile_m()), N, M, theta_b, p.dcol, p.t_b, st));
+    im.drow = p.drow; im.dcol = p.dcol; im.t_a = p.t_a; im.t_b = p.t_b;
+    // lines 8-10: Reduce -> CSR of A', CSC of B'
+    int64_t chk = select_chunks(K);
+    if (term_a) {
+      SRQ_HIP(h, launch_select_count(A, M, K, lda, SRQ_AXIS_ROW, p.t_a, p.cnt_a, st));
+      SRQ_HIP(h, launch_select_scan(p.cnt_a, M, chk, p.tot_a, p.a_ptr, p.nnz + 0, st));
+      SRQ_HIP(h, launch_select_scatter(A, M, K, lda, SRQ_AXIS_ROW, p.t_a, p.lam_a, qmax, trunc, p.a_ptr,
+                                       p.cnt_a, p.a_idx, p.a_val, p.cap_a, st));
+      im.a_ptr = p.a_ptr; im.a_idx = p.a_idx; im.a_val = p.a_val; im.capacity_a = p.cap_a;
+    }
+    if (term_b) {
+      SRQ_HIP(h, launch_select_count(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.cnt_b, st));
+      SRQ_HIP(h, launch_select_scan(p.cnt_b, N, chk, p.tot_b, p.b_ptr, p.nnz + 1, st));
+      SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
+                                       p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));
+      im.b_ptr = p.b_ptr; im.b_idx = p.b_idx; im.b_val = p.b_val; im.capacity_b = p.cap_b;
+    }
+    // line 9 and the branch of line 11: which execution each term takes
+    const bool sync_mode = strategy == SRQ_STRATEGY_AUTO || dense_fallback_density <= 1.f;
+    if (sync_mode) {
+      h->host_nnz[0] = h->host_nnz[1] = 0;
+      SRQ_HIP(h, hipMemcpyAsync(h->host_nnz, p.nnz, 2 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+      SRQ_HIP(h, hipStreamSynchronize(st));
+      int64_t na = term_a ? h->host_nnz[0] : 0, nb = term_b ? h->host_nnz[1] : 0;
+      if (na > p.cap_a || nb > p.cap_b) {
+        if (stats_dev) SRQ_HIP(h, launch_stats(term_a ? p.nnz : nullptr, term_b ? p.nnz + 1 : nullptr, 0, 0, stats_dev, st));
+        return SRQ_STATUS_CAPACITY;
+      }
+      double da = (double)na / ((double)M * (double)K), db = (double)nb / ((double)N * (double)K);
+      auto pick = [&](double d) {
+        if (d >= (double)dense_fallback_density) return 3;
+        if (strategy == SRQ_STRATEGY_AUTO) return d >= kAutoMfmaDensity ? 2 : 1;
+        return (int)strategy;
+      };
+      if (term_a) path_a = pick(da);
+      if (term_b) path_b = pick(db);
+    } else {
+      if (term_a) path_a = (int)strategy;
+      if (term_b) path_b = (int)strategy;
+    }
+    // lines 4-6: residual matrices and their codes, in the layouts the chosen paths read
+    // (RA feeds term 2, RB feeds term 1)
+    bool ra_vm = path_b >= 2, ra_em = path_b == 1, rb_vm = path_a >= 2, rb_em = path_a == 1;
+    if (ra_vm || ra_em)
+      SRQ_HIP(h, launch_residual_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, p.lam_ra, qmax, trunc,
+                                       ra_vm ? p.RA_int : nullptr, K, ra_em ? p.RA_em : nullptr, M, st));
+    if (rb_vm || rb_em)
+      SRQ_HIP(h, launch_residual_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, p.lam_rb, qmax, trunc,
+                                       rb_vm ? p.RB_int : nullptr, K, rb_em ? p.RB_em : nullptr, N, st));
+    if (ra_vm) im.RA_int = p.RA_int;
+    if (ra_em) im.RA_em = p.RA_em;
+    if (rb_vm) im.RB_int = p.RB_int;
+    if (rb_em) im.RB_em = p.RB_em;
+
+    // lines 11-17: correction terms, accumulated into C in the order DR1 then DR2
+    GemmEpilogue e1 = ep;
+    e1.mode = kGemmAccum; e1.row_part = e1.col_part = nullptr; e1.D_F_copy = nullptr;
+    e1.s_row = p.s_a; e1.s_col = p.s_rb;
+    e1.D_int = dbg ? dbg->DR1_int : nullptr;
+    e1.final_scale = scale_needed && path_b == 0;
+    if (path_a == 1) {
+      SRQ_HIP(h, launch_spmm_valu(0, M, N, p.a_ptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, e1, st));
+    } else if (path_a == 2) {
+      SRQ_HIP(h, launch_densify(p.a_ptr, p.a_idx, p.a_val, M, K, p.cap_a, p.Ad, K, st));
+      SRQ_HIP(h, launch_gemm_i8(M, N, K, p.Ad, K, p.RB_int, K, e1, st));
+    } else if (path_a == 3) {
+      SRQ_HIP(h, launch_gemm_i8(M, N, K, p.A_int, K, p.RB_int, K, e1, st));
+    }
+    GemmEpilogue e2 = e1;
+    e2.s_row = p.s_ra; e2.s_col = p.s_b;
+    e2.D_int = dbg ? dbg->DR2_int : nullptr;
+    e2.final_scale = scale_needed;
+    if (path_b == 1) {
+      SRQ_HIP(h, launch_spmm_valu(1, N, M, p.b_ptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, e2, st));
+    } else if (path_b == 2) {
+      SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, K, st));
+      SRQ_HIP(h, launch_gemm_i8(M, N, K, p.RA_int, K, p.Bd, K, e2, st));
+    } else if (path_b == 3) {
+      SRQ_HIP(h, launch_gemm_i8(M, N, K, p.RA_int, K, p.B_int, K, e2, st));
+    }
+    if (scale_needed && path_a == 0 && path_b == 0) {
+      GemmEpilogue e3 = ep;
+      SRQ_HIP(h, launch_scale_only(M, N, e3, st));
+    }
+  }
+  if (stats_dev)
+    SRQ_HIP(h, launch_stats(path_a ? p.nnz : nullptr, path_b ? p.nnz + 1 : nullptr, path_a, path_b, stats_dev, st));
+  return SRQ_STATUS_OK;
+}
+
+}  // extern "C"

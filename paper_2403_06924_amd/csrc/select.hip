@@ -1,0 +1,261 @@
+// Reduction of the operands to sparse matrices (Algorithm 1 lines 7-10; Eq. avgQuan):
+// thresholds from the means of |D_F|, threshold-select, and stream compaction to CSR / CSC
+// by count -> exclusive prefix scan -> scatter.  All integer work is deterministic.
+#include "srq_internal.h"
+
+namespace srq {
+namespace {
+
+__device__ __forceinline__ int quant_code(float x, float lam, float qmax, int trunc) {
+  float y = x * lam;
+  float r = trunc ? truncf(y) : rintf(y);
+  r = fminf(fmaxf(r, -qmax), qmax);
+  return (int)r;
+}
+
+// mean_v = (sum over partial sums, fixed order) / count, rounded once to float;
+// thresh_v = fl(theta * mean_v)
+__global__ void reduce_means_kernel(const double* __restrict__ part, int64_t nparts, int64_t nvec,
+                                    double count, float theta, float* __restrict__ mean,
+                                    float* __restrict__ thresh) {
+  int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= nvec) return;
+  double s = 0.0;
+  for (int64_t p = 0; p < nparts; ++p) s += part[p * nvec + v];
+  float m = (float)(s / count);
+  if (mean) mean[v] = m;
+  if (thresh) thresh[v] = theta * m;
+}
+
+// ---- vectors are rows: one wave per (row, chunk of kSelChunk consecutive elements) ----
+template <bool SCATTER>
+__global__ __launch_bounds__(256) void select_rows_kernel(
+    const float* __restrict__ X, int64_t rows, int64_t cols, int64_t ldx, const float* __restrict__ thresh,
+    const float* __restrict__ lambda, float qmax, int trunc, int64_t nchunks, int32_t* __restrict__ cnt,
+    const int32_t* __restrict__ ptr, const int32_t* __restrict__ off, int32_t* __restrict__ idx,
+    int8_t* __restrict__ val, int64_t capacity) {
+  int lane = threadIdx.x & 63;
+  int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  int64_t v = g / nchunks, ch = g - v * nchunks;
+  if (v >= rows) return;
+  float t = thresh[v];
+  float lam = SCATTER ? lambda[v] : 0.f;
+  const float* row = X + v * ldx;
+  int64_t base = 0;
+  if (SCATTER) base = (int64_t)ptr[v] + off[ch * rows + v];
+  int total = 0;
+  int64_t e0 = ch * kSelChunk;
+#pragma unroll
+  for (int it = 0; it < kSelChunk / 64; ++it) {
+    int64_t e = e0 + it * 64 + lane;
+    float x = 0.f;
+    bool keep = false;
+    if (e < cols) {
+      x = row[e];
+      keep = fabsf(x) > t;
+    }
+    unsigned long long m = __ballot(keep);
+    if (SCATTER) {
+      if (keep) {
+        int64_t pos = base + total + __popcll(m & ((1ull << lane) - 1ull));
+        if (pos < capacity) {
+          idx[pos] = (int32_t)e;
+          val[pos] = (int8_t)quant_code(x, lam, qmax, trunc);
+        }
+      }
+    }
+    total += __popcll(m);
+  }
+  if (!SCATTER && lane == 0) cnt[ch * rows + v] = total;
+}
+
+// ---- vectors are columns: lane = column, one wave per (64 columns, chunk of rows) ----
+template <bool SCATTER>
+__global__ __launch_bounds__(256) void select_cols_kernel(
+    const float* __restrict__ X, int64_t rows, int64_t cols, int64_t ldx, const float* __restrict__ thresh,
+    const float* __restrict__ lambda, float qmax, int trunc, int64_t nchunks, int32_t* __restrict__ cnt,
+    const int32_t* __restrict__ ptr, const int32_t* __restrict__ off, int32_t* __restrict__ idx,
+    int8_t* __restrict__ val, int64_t capacity) {
+  int lane = threadIdx.x & 63;
+  int64_t ch = (int64_t)blockIdx.y * 4 + (threadIdx.x >> 6);
+  int64_t v = (int64_t)blockIdx.x * 64 + lane;
+  if (ch >= nchunks || v >= cols) return;
+  float t = thresh[v];
+  float lam = SCATTER ? lambda[v] : 0.f;
+  int64_t pos = 0;
+  if (SCATTER) pos = (int64_t)ptr[v] + off[ch * cols + v];
+  int64_t r0 = ch * kSelChunk;
+  int64_t r1 = r0 + kSelChunk < rows ? r0 + kSelChunk : rows;
+  int total = 0;
+#pragma unroll 8
+  for (int64_t r = r0; r < r1; ++r) {
+    float x = X[r * ldx + v];
+    if (fabsf(x) > t) {
+      if (SCATTER) {
+        if (pos < capacity) {
+          idx[pos] = (int32_t)r;
+          val[pos] = (int8_t)quant_code(x, lam, qmax, trunc);
+        }
+        ++pos;
+      }
+      ++total;
+    }
+  }
+  if (!SCATTER) cnt[ch * cols + v] = total;
+}
+
+// counts[chunk][vec] -> exclusive offsets within the vector (in place) and totals[vec]
+__global__ void chunk_offsets_kernel(int32_t* __restrict__ cnt_then_off, int64_t nvec, int64_t nchunks,
+                                     int32_t* __restrict__ totals) {
+  int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= nvec) return;
+  int32_t run = 0;
+  for (int64_t c = 0; c < nchunks; ++c) {
+    int32_t n = cnt_then_off[c * nvec + v];
+    cnt_then_off[c * nvec + v] = run;
+    run += n;
+  }
+  totals[v] = run;
+}
+
+// exclusive prefix scan of totals[nvec] into ptr[nvec+1], one 1024-thread block
+__global__ __launch_bounds__(1024) void scan_totals_kernel(const int32_t* __restrict__ totals, int64_t nvec,
+                                                           int32_t* __restrict__ ptr,
+                                                           int64_t* __restrict__ nnz_dev) {
+  __shared__ int64_t wave_sum[16];
+  __shared__ int64_t carry_s;
+  int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  for (int64_t base = 0; base < nvec; base += 1024) {
+    int64_t v = base + tid;
+    int64_t x = v < nvec ? totals[v] : 0;
+    int64_t inc = x;                                   // inclusive scan within the wave
+    for (int d = 1; d < 64; d <<= 1) {
+      int64_t y = __shfl_up(inc, d, 64);
+      if (lane >= d) inc += y;
+    }
+    if (lane == 63) wave_sum[w] = inc;
+    __syncthreads();
+    int64_t wave_off = 0;
+    for (int i = 0; i < w; ++i) wave_off += wave_sum[i];
+    int64_t carry = carry_s;
+    if (v < nvec) ptr[v] = (int32_t)(carry + wave_off + inc - x);
+    __syncthreads();
+    if (tid == 1023) carry_s = carry + wave_off + inc;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    ptr[nvec] = (int32_t)carry_s;
+    if (nnz_dev) *nnz_dev = carry_s;
+  }
+}
+
+// one block per vector: zero the dense vector, then drop the kept codes in
+__global__ __launch_bounds__(256) void densify_kernel(const int32_t* __restrict__ ptr,
+                                                      const int32_t* __restrict__ idx,
+                                                      const int8_t* __restrict__ val, int64_t veclen,
+                                                      int64_t capacity, int8_t* __restrict__ dense,
+                                                      int64_t ld) {
+  int64_t v = blockIdx.x;
+  int8_t* row = dense + v * ld;
+  if ((reinterpret_cast<uintptr_t>(row) & 15) == 0) {
+    int64_t n16 = veclen / 16;
+    int4 z = make_int4(0, 0, 0, 0);
+    for (int64_t i = threadIdx.x; i < n16; i += 256) reinterpret_cast<int4*>(row)[i] = z;
+    for (int64_t i = n16 * 16 + threadIdx.x; i < veclen; i += 256) row[i] = 0;
+  } else {
+    for (int64_t i = threadIdx.x; i < veclen; i += 256) row[i] = 0;
+  }
+  __syncthreads();
+  int64_t p0 = ptr[v], p1 = ptr[v + 1];
+  if (p1 > capacity) p1 = capacity;
+  for (int64_t p = p0 + threadIdx.x; p < p1; p += 256) row[idx[p]] = val[p];
+}
+
+__global__ void stats_kernel(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b,
+                             srq_stats_t* out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    out->nnz_a = nnz_a ? *nnz_a : 0;
+    out->nnz_b = nnz_b ? *nnz_b : 0;
+    out->path_a = path_a;
+    out->path_b = path_b;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_reduce_means(const double* part, int64_t nparts, int64_t nvec, int64_t count,
+                               float theta, float* mean, float* thresh, hipStream_t st) {
+  if (nvec <= 0) return hipSuccess;
+  hipLaunchKernelGGL(reduce_means_kernel, dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, part,
+                     nparts, nvec, (double)count, theta, mean, thresh);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_count(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
+                               const float* thresh, int32_t* cnt, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  if (axis == SRQ_AXIS_ROW) {
+    int64_t nch = select_chunks(cols);
+    int64_t waves = rows * nch;
+    hipLaunchKernelGGL(select_rows_kernel<false>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, X,
+                       rows, cols, ldx, thresh, nullptr, 0.f, 0, nch, cnt, nullptr, nullptr, nullptr,
+                       nullptr, 0);
+  } else {
+    int64_t nch = select_chunks(rows);
+    dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((nch + 3) / 4));
+    hipLaunchKernelGGL(select_cols_kernel<false>, grid, dim3(256), 0, st, X, rows, cols, ldx, thresh,
+                       nullptr, 0.f, 0, nch, cnt, nullptr, nullptr, nullptr, nullptr, 0);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_select_scan(int32_t* cnt_then_off, int64_t nvec, int64_t nchunks, int32_t* totals,
+                              int32_t* ptr, int64_t* nnz_dev, hipStream_t st) {
+  if (nvec > 0 && nchunks > 0)
+    hipLaunchKernelGGL(chunk_offsets_kernel, dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st,
+                       cnt_then_off, nvec, nchunks, totals);
+  else if (nvec > 0) {
+    hipError_t e = launch_fill_u32(reinterpret_cast<uint32_t*>(totals), nvec, 0, st);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(scan_totals_kernel, dim3(1), dim3(1024), 0, st, totals, nvec, ptr, nnz_dev);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_scatter(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
+                                 const float* thresh, const float* lambda, int qmax, int trunc,
+                                 const int32_t* ptr, const int32_t* off, int32_t* idx, int8_t* val,
+                                 int64_t capacity, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  if (axis == SRQ_AXIS_ROW) {
+    int64_t nch = select_chunks(cols);
+    int64_t waves = rows * nch;
+    hipLaunchKernelGGL(select_rows_kernel<true>, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, X,
+                       rows, cols, ldx, thresh, lambda, (float)qmax, trunc, nch, nullptr, ptr, off, idx,
+                       val, capacity);
+  } else {
+    int64_t nch = select_chunks(rows);
+    dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((nch + 3) / 4));
+    hipLaunchKernelGGL(select_cols_kernel<true>, grid, dim3(256), 0, st, X, rows, cols, ldx, thresh,
+                       lambda, (float)qmax, trunc, nch, nullptr, ptr, off, idx, val, capacity);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* val, int64_t nvec,
+                          int64_t veclen, int64_t capacity, int8_t* dense, int64_t ld, hipStream_t st) {
+  if (nvec <= 0 || veclen <= 0) return hipSuccess;
+  hipLaunchKernelGGL(densify_kernel, dim3((unsigned)nvec), dim3(256), 0, st, ptr, idx, val, veclen,
+                     capacity, dense, ld);
+  return hipGetLastError();
+}
+
+hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b,
+                        srq_stats_t* out, hipStream_t st) {
+  hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(64), 0, st, nnz_a, nnz_b, path_a, path_b, out);
+  return hipGetLastError();
+}
+
+}  // namespace srq

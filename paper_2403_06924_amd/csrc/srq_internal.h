@@ -1,0 +1,100 @@
+// Internal declarations shared by the translation units of libsrq (not part of the ABI).
+#ifndef SRQ_INTERNAL_H_
+#define SRQ_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "srq.h"
+
+struct srq_context {
+  int device;            // -1: no device (validation only)
+  void* ws;              // caller-owned device workspace
+  size_t ws_bytes;
+  int last_hip_error;
+  int64_t* host_nnz;     // pinned host buffer for the two counters read back in synchronising modes
+  srq_intermediates_t last;
+};
+
+namespace srq {
+
+inline int qmax_of_bits(int bits) { return (1 << (bits - 1)) - 1; }
+
+constexpr int kSelChunk = 256;      // elements of a vector handled by one wave in count/scatter
+
+// epilogue modes of the INT8 GEMM
+enum GemmMode { kGemmFirst = 0, kGemmAccum = 1 };
+
+struct GemmEpilogue {
+  int mode;               // GemmMode
+  const float* s_row;     // [M] scale paired with rows of the output
+  const float* s_col;     // [N] scale paired with columns
+  float* C;               // output / accumulator, row-major
+  int64_t ldc;
+  int32_t* D_int;         // optional raw INT32 product (ld = ldd), may be null
+  int64_t ldd;
+  float* D_F_copy;        // optional copy of the dequantized product before alpha/beta (ld = ldd)
+  double* row_part;       // kGemmFirst: [tiles_n][M] partial sums of |D_F| (may be null)
+  double* col_part;       // kGemmFirst: [tiles_m][N]
+  int final_scale;        // apply alpha/beta after this term
+  float alpha, beta;
+  const float* Cin;
+  int64_t ldcin;
+};
+
+// ---- launchers (each returns the hipError_t of its launches) --------------------------
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
+
+// amax of |x| per vector as float bits in amax_bits[nvec] (must be zero-filled for AXIS_COL)
+hipError_t launch_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
+                       uint32_t* amax_bits, hipStream_t st);
+// in place: amax bits -> scale = amax/qmax; lambda = qmax/amax (lambda may be null)
+hipError_t launch_scales(uint32_t* amax_bits_then_scale, float* lambda, int64_t nvec, int qmax,
+                         hipStream_t st);
+// codes of X in `layout`; if ramax_bits != null also accumulates max|residual| per vector
+hipError_t launch_quantize_tiles(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
+                                 const float* scale, const float* lambda, int qmax, int trunc,
+                                 int layout, int8_t* Q, int64_t ldq, uint32_t* ramax_bits,
+                                 hipStream_t st);
+// residual codes in up to two layouts (either output may be null)
+hipError_t launch_residual_tiles(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
+                                 const float* scale, const float* lambda, const float* rlambda,
+                                 int qmax, int trunc, int8_t* R_vm, int64_t ld_vm, int8_t* R_em,
+                                 int64_t ld_em, hipStream_t st);
+
+// selection: counts per (chunk, vector) -> offsets -> compacted arrays
+hipError_t launch_select_count(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
+                               const float* thresh, int32_t* cnt, hipStream_t st);
+hipError_t launch_select_scan(int32_t* cnt_then_off, int64_t nvec, int64_t nchunks, int32_t* totals,
+                              int32_t* ptr, int64_t* nnz_dev, hipStream_t st);
+hipError_t launch_select_scatter(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
+                                 const float* thresh, const float* lambda, int qmax, int trunc,
+                                 const int32_t* ptr, const int32_t* off, int32_t* idx, int8_t* val,
+                                 int64_t capacity, hipStream_t st);
+inline int64_t select_chunks(int64_t veclen) { return (veclen + kSelChunk - 1) / kSelChunk; }
+
+// thresholds from the partial sums of the GEMM epilogue
+hipError_t launch_reduce_means(const double* part, int64_t nparts, int64_t nvec, int64_t count,
+                               float theta, float* mean, float* thresh, hipStream_t st);
+
+// INT8 GEMM, both operands K-contiguous
+int gemm_tile_m();
+int gemm_tile_n();
+hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
+                          const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st);
+
+// CSR (vector-major) -> zero-filled dense vector-major codes
+hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* val, int64_t nvec,
+                          int64_t veclen, int64_t capacity, int8_t* dense, int64_t ld, hipStream_t st);
+
+// VALU SpMM.  out[v, e] = sum_p val[p] * R[idx[p]*ldr + e];  side 0: C[v, e], side 1: C[e, v]
+hipError_t launch_spmm_valu(int side, int64_t nvec, int64_t nelem, const int32_t* ptr,
+                            const int32_t* idx, const int8_t* val, int64_t capacity, const int8_t* R,
+                            int64_t ldr, const GemmEpilogue& ep, hipStream_t st);
+
+hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b,
+                        srq_stats_t* out, hipStream_t st);
+hipError_t launch_scale_only(int64_t M, int64_t N, const GemmEpilogue& ep, hipStream_t st);
+
+}  // namespace srq
+#endif

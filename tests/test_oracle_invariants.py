@@ -36,7 +36,7 @@ def test_int_matmul_brute_force(shape):
 
 
 def test_int_matmul_worst_case_at_k_bound():
-    K = (2 ** 31 - 1) // (127 * 127)                 # 133143, the largest K allowed
+    K = (2 ** 31 - 1) // (127 * 127)                 # 133144, the largest K allowed
     o.check_k_bound(K, 127)
     with pytest.raises(OverflowError):
         o.check_k_bound(K + 1, 127)
