@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Throughput of the sparse-residual-compensated INT8 GEMM on one MI355X.
+
+One step = one srq_compensated_gemm call: FP32 A, B resident in HBM -> FP32 C in HBM, every
+step of Algorithm 1 (quantize, INT8 GEMM, dequantize, means, residual codes, threshold-select
+and compaction, sparse correction products, epilogue).  Prints ONE JSON line:
+effective TOPS = 2MNK / t, the roofline of the dominant kernel from HIP events recorded on
+the launch stream inside the timed region, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0       # MI355X dense INT8 MFMA peak, 5.0 POP/s
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, 8 TB/s
+# plain vector ALU integer multiply-add: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz x 2 ops
+PEAK_VALU_INT_TOPS = 256 * 4 * 16 * 2.4e9 * 2 / 1e12
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C3", help="C1..C5 (default C3: 8192^3 with outliers)")
+    ap.add_argument("--density", type=float, default=None, help="target density of A' and B'")
+    ap.add_argument("--strategy", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--dense-fallback", type=float, default=2.0, help="Algorithm 1's limit s (>1: off)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-accuracy", action="store_true")
+    ap.add_argument("--report", default=None, help="also write the full report to this JSON file")
+    return ap.parse_args()
+
+
+def calibrate_theta(torch, X, dvec, axis, density):
+    """Harness only: theta such that about `density` of the entries have |x| > theta*dvec."""
+    d = dvec.view(-1, 1) if axis == 0 else dvec.view(1, -1)
+    rho = (X.abs() / d).reshape(-1)
+    keep = int(round(rho.numel() * density))
+    if keep <= 0:
+        return float("inf")
+    if keep >= rho.numel():
+        return 0.0
+    k = rho.numel() - keep
+    return float(torch.kthvalue(rho, k).values.item())
+
+
+def cpu_baseline(name, A, B, theta_a, theta_b):
+    """The oracle as it stands, on a bounded sample: the first rows of A against all of B."""
+    import numpy as np
+    from oracle import srq_oracle as o
+    M, K = A.shape
+    N = B.shape[1]
+    budget = 4.0e11                                   # about 10-30 s of oracle work
+    per_row = 3.0 * 2.0 * N * K
+    ms = int(max(64, min(M, budget // per_row)))
+    As = np.ascontiguousarray(A[:ms])
+    t0 = time.perf_counter()
+    o.compensated_gemm(As, B, theta_a, theta_b)
+    dt = time.perf_counter() - t0
+    try:
+        import threadpoolctl
+        cores = max(int(i.get("num_threads", 1)) for i in threadpoolctl.threadpool_info()) \
+            if threadpoolctl.threadpool_info() else os.cpu_count()
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": 2.0 * ms * N * K / dt / 1e12, "unit": "TOPS", "cores": int(cores), "kind": "oracle",
+            "sample": "rows 0..%d of A against all of B (M=%d, N=%d, K=%d), full Algorithm 1, %.1f s"
+                      % (ms - 1, ms, N, K, dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build measures one GPU only (the path is a single-device "
+                         "kernel pipeline; see DESIGN.md for how it would shard); run with --gpus 1\n")
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2403_06924_amd import binding as b
+    from paper_2403_06924_amd import workloads as wl
+
+    if not os.path.exists(b.LIB_PATH):
+        from paper_2403_06924_amd import build
+        build.build()
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py needs a GPU\n")
+        sys.exit(3)
+    w = wl.WORKLOADS[args.workload]
+    density = args.density if args.density is not None else w.densities[0 if len(w.densities) == 1 else 1]
+    M, N, K = w.M, w.N, w.K
+    A, B = wl.make_inputs(w.name)
+    Ad, Bd = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    h = b.Srq(device=0)
+
+    # threshold factors for the requested density, from the GPU's own first product
+    Qa, sa, _ = h.quantize(Ad, b.AXIS_ROW)
+    Qb, sb, _ = h.quantize(Bd, b.AXIS_COL)
+    _, _, drow, dcol = h.gemm_i8(Qa, sa, Qb, sb)
+    theta_a = calibrate_theta(torch, Ad, drow, 0, density)
+    theta_b = calibrate_theta(torch, Bd, dcol, 1, density)
+    del Qa, Qb
+    torch.cuda.empty_cache()
+
+    strategy = {"auto": b.STRATEGY_AUTO, "valu": b.STRATEGY_CSR_VALU, "mfma": b.STRATEGY_CSR_MFMA}[args.strategy]
+    stats = b.stats_tensor()
+    Cd = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    max_density = min(1.0, density * 1.25 + 0.01)
+
+    def step():
+        h.compensated_gemm(Ad, Bd, theta_a, theta_b, strategy=strategy,
+                           dense_fallback_density=args.dense_fallback, out=Cd, stats=stats,
+                           max_density=max_density)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    h.profile_enable(True)
+    stage_ms = {k: 0.0 for k in b.STAGES}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+        for k, v in h.profile_read().items():       # waits for this step's events
+            stage_ms[k] += v
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    h.profile_enable(False)
+    ms_per_step = dt / args.steps * 1e3
+    stage_ms = {k: v / args.steps for k, v in stage_ms.items()}
+    st = b.read_stats(stats)
+    ops = 2.0 * M * N * K
+    value = ops / (ms_per_step * 1e-3) / 1e12
+
+    # roofline of the dominant kernel.  The INT8 GEMM kernel runs once for the first product
+    # and once per correction term that takes a matrix-core path (2 = expanded CSR, 3 = dense)
+    gemm_ms = [stage_ms["gemm"]]
+    valu_ms = []
+    for term, path in (("term1", st["path_a"]), ("term2", st["path_b"])):
+        if path in (2, 3):
+            gemm_ms.append(stage_ms[term])
+        elif path == 1:
+            valu_ms.append((stage_ms[term], st["nnz_a"] * N if term == "term1" else st["nnz_b"] * M))
+    if sum(gemm_ms) >= sum(t for t, _ in valu_ms):
+        avg = sum(gemm_ms) / len(gemm_ms)
+        ach = ops / (avg * 1e-3) / 1e12
+        roof = {"kernel": "gemm_i8_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_INT8_TOPS,
+                "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS, "traffic": None,
+                "launches_per_step": len(gemm_ms), "avg_launch_ms": avg}
+    else:
+        t = sum(t for t, _ in valu_ms)
+        macs = sum(m for _, m in valu_ms)
+        ach = 2.0 * macs / (t * 1e-3) / 1e12
+        roof = {"kernel": "spmm_valu_kernel", "bound": "alu", "achieved": ach, "peak": PEAK_VALU_INT_TOPS,
+                "unit": "TOP/s", "frac": ach / PEAK_VALU_INT_TOPS, "traffic": None,
+                "launches_per_step": len(valu_ms), "avg_launch_ms": t / len(valu_ms)}
+
+    accuracy = None
+    if not args.no_accuracy:
+        C64 = Ad.double() @ Bd.double()
+        nrm = torch.linalg.norm(C64)
+        e_comp = float(torch.linalg.norm(C64 - Cd.double()) / nrm)
+        inf = float("inf")
+        h.compensated_gemm(Ad, Bd, inf, inf, out=Cd)
+        e_plain = float(torch.linalg.norm(C64 - Cd.double()) / nrm)
+        h.compensated_gemm(Ad, Bd, 0.0, 0.0, strategy=b.STRATEGY_CSR_MFMA, dense_fallback_density=0.0, out=Cd)
+        e_dense = float(torch.linalg.norm(C64 - Cd.double()) / nrm)
+        accuracy = {"rel_err_vs_fp64_plain_int8": e_plain, "rel_err_vs_fp64_compensated": e_comp,
+                    "rel_err_vs_fp64_dense_residual": e_dense}
+        del C64
+
+    out = {
+        "metric": "effective TOPS (2MNK/s) of compensated INT8 GEMM", "value": value, "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": "%s: M=%d N=%d K=%d, %s, seed %d" % (w.name, M, N, K, w.recipe, w.seed),
+                   "target_density": density, "theta_a": theta_a, "theta_b": theta_b,
+                   "strategy": args.strategy, "dense_fallback_density": args.dense_fallback,
+                   "bits": 8, "rounding": "nearest_even"},
+        "frac_of_int8_mfma_peak": value / PEAK_INT8_TOPS,
+        "density_a": st["nnz_a"] / (M * K), "density_b": st["nnz_b"] / (N * K),
+        "path_a": st["path_a"], "path_b": st["path_b"],
+        "stage_ms": stage_ms,
+        "roofline": roof,
+        "accuracy": accuracy,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w.name, A, B, theta_a, theta_b)
+    line = json.dumps(out)
+    if args.report:
+        os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
+        with open(args.report, "w") as f:
+            f.write(json.dumps(out, indent=1) + "\n")
+    print(line)
+    h.close()
+
+
+if __name__ == "__main__":
+    main()

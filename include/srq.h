@@ -118,6 +118,24 @@ srq_status_t srq_workspace_bytes(int64_t M, int64_t N, int64_t K, double max_den
 srq_status_t srq_set_workspace(srq_handle_t handle, void* workspace, size_t bytes);
 srq_status_t srq_stage_workspace_bytes(int64_t M, int64_t N, int64_t K, size_t* bytes);
 
+/* Stage timing of srq_compensated_gemm (the per-stage time shares of Sec. 4.1.2).  When
+ * enabled, the call records a pair of HIP events on `stream` around each stage;
+ * srq_profile_read waits for them and writes the milliseconds of the last call's stages
+ * to ms[SRQ_NUM_STAGES] (host array; 0 for a stage that did not run). */
+enum {
+  SRQ_STAGE_QUANTIZE = 0,   /* amax, scales, codes of A and B, max |residual|             */
+  SRQ_STAGE_GEMM = 1,       /* INT8 product, dequantization, partial sums of |D_F|        */
+  SRQ_STAGE_SELECT = 2,     /* means, thresholds, count / scan / scatter to CSR and CSC   */
+  SRQ_STAGE_RESIDUAL = 3,   /* residual codes in the layouts the chosen paths read        */
+  SRQ_STAGE_TERM1_PREP = 4, /* expansion of CSR(A') for the matrix-core path              */
+  SRQ_STAGE_TERM1 = 5,      /* DR1 product + accumulate                                   */
+  SRQ_STAGE_TERM2_PREP = 6,
+  SRQ_STAGE_TERM2 = 7,
+  SRQ_NUM_STAGES = 8
+};
+srq_status_t srq_profile_enable(srq_handle_t handle, int enable);
+srq_status_t srq_profile_read(srq_handle_t handle, float* ms);
+
 /* Last hipError_t seen by this handle as an int (0 = hipSuccess).  Host call. */
 int srq_last_hip_error(srq_handle_t handle);
 const char* srq_status_string(srq_status_t status);

@@ -25,8 +25,9 @@ EXPORTS = [
     "srq_create", "srq_destroy", "srq_workspace_bytes", "srq_set_workspace",
     "srq_stage_workspace_bytes", "srq_last_hip_error", "srq_status_string", "srq_quantize",
     "srq_build_sparse_residual", "srq_gemm_i8", "srq_spmm_accumulate", "srq_compensated_gemm",
-    "srq_get_intermediates",
+    "srq_get_intermediates", "srq_profile_enable", "srq_profile_read",
 ]
+STAGES = ["quantize", "gemm", "select", "residual", "term1_prep", "term1", "term2_prep", "term2"]
 
 
 class Stats(C.Structure):
@@ -82,6 +83,8 @@ def load():
     lib.srq_compensated_gemm.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, f32, f32, i32, i32, f32, i32,
                                          f32, f32, vp, i64, vp, i64, vp, C.POINTER(Debug), vp]
     lib.srq_get_intermediates.argtypes = [vp, C.POINTER(Intermediates)]
+    lib.srq_profile_enable.argtypes = [vp, i32]
+    lib.srq_profile_read.argtypes = [vp, C.POINTER(f32)]
     for name in EXPORTS:
         if name != "srq_status_string":
             getattr(lib, name).restype = i32
@@ -171,6 +174,15 @@ class Srq:
         off = ptr - self.ws.data_ptr()
         nbytes = count * torch.empty((), dtype=dtype).element_size()
         return self.ws[off:off + nbytes].view(dtype)
+
+    def profile_enable(self, on=True):
+        self._ret(self.lib.srq_profile_enable(self.h, 1 if on else 0), "srq_profile_enable")
+
+    def profile_read(self):
+        """Milliseconds per stage of the last compensated_gemm call (waits for its events)."""
+        ms = (C.c_float * len(STAGES))()
+        self._ret(self.lib.srq_profile_read(self.h, ms), "srq_profile_read")
+        return dict(zip(STAGES, [float(x) for x in ms]))
 
     # -- entry points -----------------------------------------------------------------
     def quantize(self, X, axis, bits=8, rounding=ROUND_NEAREST_EVEN, layout=LAYOUT_VECTOR_MAJOR):

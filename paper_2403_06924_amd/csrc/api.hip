@@ -127,6 +127,21 @@ srq_status_t check_common(srq_handle_t h, int bits) {
 
 bool k_overflows(int64_t K, int qmax) { return K * (int64_t)qmax * qmax >= (1LL << 31); }
 
+struct StageTimer {
+  srq_handle_t h;
+  hipStream_t st;
+  int id;
+  StageTimer(srq_handle_t h_, hipStream_t st_, int id_) : h(h_), st(st_), id(id_) {
+    if (h->prof_enabled) {
+      (void)hipEventRecord(h->prof_ev[2 * id], st);
+      h->prof_used |= 1u << id;
+    }
+  }
+  ~StageTimer() {
+    if (h->prof_enabled) (void)hipEventRecord(h->prof_ev[2 * id + 1], st);
+  }
+};
+
 srq_status_t bind_device(srq_handle_t h) {
   if (h->device < 0) return SRQ_STATUS_NO_DEVICE;
   SRQ_HIP(h, hipSetDevice(h->device));
@@ -170,8 +185,35 @@ srq_status_t srq_create(srq_handle_t* handle, int device) {
   return SRQ_STATUS_OK;
 }
 
+srq_status_t srq_profile_enable(srq_handle_t h, int enable) {
+  if (!h) return SRQ_STATUS_INVALID_ARG;
+  if (enable && !h->prof_created) {
+    srq_status_t s = bind_device(h);
+    if (s) return s;
+    for (int i = 0; i < 2 * SRQ_NUM_STAGES; ++i) SRQ_HIP(h, hipEventCreate(&h->prof_ev[i]));
+    h->prof_created = 1;
+  }
+  h->prof_enabled = enable ? 1 : 0;
+  h->prof_used = 0;
+  return SRQ_STATUS_OK;
+}
+
+srq_status_t srq_profile_read(srq_handle_t h, float* ms) {
+  if (!h || !ms) return SRQ_STATUS_INVALID_ARG;
+  for (int i = 0; i < SRQ_NUM_STAGES; ++i) {
+    ms[i] = 0.f;
+    if (h->prof_created && (h->prof_used & (1u << i))) {
+      SRQ_HIP(h, hipEventSynchronize(h->prof_ev[2 * i + 1]));
+      SRQ_HIP(h, hipEventElapsedTime(&ms[i], h->prof_ev[2 * i], h->prof_ev[2 * i + 1]));
+    }
+  }
+  return SRQ_STATUS_OK;
+}
+
 srq_status_t srq_destroy(srq_handle_t h) {
   if (!h) return SRQ_STATUS_INVALID_ARG;
+  if (h->prof_created)
+    for (int i = 0; i < 2 * SRQ_NUM_STAGES; ++i) (void)hipEventDestroy(h->prof_ev[i]);
   if (h->host_nnz) (void)hipHostFree(h->host_nnz);
   delete h;
   return SRQ_STATUS_OK;
@@ -435,7 +477,10 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   memset(&im, 0, sizeof(im));
   im.A_int = p.A_int; im.B_int = p.B_int; im.s_a = p.s_a; im.lam_a = p.lam_a; im.s_b = p.s_b; im.lam_b = p.lam_b;
 
+  h->prof_used = 0;
   // lines 1: Quant.  amax per vector -> scale, lambda -> codes (and max |residual| per vector)
+  {
+  StageTimer tm(h, st, SRQ_STAGE_QUANTIZE);
   SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_a), M, 0, st));
   SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_b), N, 0, st));
   if (comp) {
@@ -457,6 +502,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_rb), p.lam_rb, N, qmax, st));
     im.s_ra = p.s_ra; im.s_rb = p.s_rb;
   }
+  }
 
   // lines 2-3: D_int = A_int.B_int, D_F = dequant; line 7: partial sums of |D_F|
   GemmEpilogue ep;
@@ -468,9 +514,14 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   if (dbg) { ep.D_int = dbg->D_int; ep.D_F_copy = dbg->D_F; }
   if (comp) { ep.row_part = p.row_part; ep.col_part = p.col_part; }
   ep.final_scale = !comp && scale_needed;
-  SRQ_HIP(h, launch_gemm_i8(M, N, K, p.A_int, K, p.B_int, K, ep, st));
+  {
+    StageTimer tm(h, st, SRQ_STAGE_GEMM);
+    SRQ_HIP(h, launch_gemm_i8(M, N, K, p.A_int, K, p.B_int, K, ep, st));
+  }
   int path_a = 0, path_b = 0;
   if (comp) {
+    {
+    StageTimer tm(h, st, SRQ_STAGE_SELECT);
     // line 7: GetAvgVec, and the thresholds of Eq. avgQuan
     SRQ_HIP(h, launch_reduce_means(p.row_part, tiles(N, gemm_tile_n()), M, N, theta_a, p.drow, p.t_a, st));
     SRQ_HIP(h, launch_reduce_means(p.col_part, tiles(M, gemm_tile_m()), N, M, theta_b, p.dcol, p.t_b, st));
@@ -490,6 +541,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
                                        p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));
       im.b_ptr = p.b_ptr; im.b_idx = p.b_idx; im.b_val = p.b_val; im.capacity_b = p.cap_b;
+    }
     }
     // line 9 and the branch of line 11: which execution each term takes
     const bool sync_mode = strategy == SRQ_STRATEGY_AUTO || dense_fallback_density <= 1.f;
@@ -517,12 +569,15 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // lines 4-6: residual matrices and their codes, in the layouts the chosen paths read
     // (RA feeds term 2, RB feeds term 1)
     bool ra_vm = path_b >= 2, ra_em = path_b == 1, rb_vm = path_a >= 2, rb_em = path_a == 1;
+    {
+    StageTimer tm(h, st, SRQ_STAGE_RESIDUAL);
     if (ra_vm || ra_em)
       SRQ_HIP(h, launch_residual_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, p.lam_ra, qmax, trunc,
                                        ra_vm ? p.RA_int : nullptr, K, ra_em ? p.RA_em : nullptr, M, st));
     if (rb_vm || rb_em)
       SRQ_HIP(h, launch_residual_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, p.lam_rb, qmax, trunc,
                                        rb_vm ? p.RB_int : nullptr, K, rb_em ? p.RB_em : nullptr, N, st));
+    }
     if (ra_vm) im.RA_int = p.RA_int;
     if (ra_em) im.RA_em = p.RA_em;
     if (rb_vm) im.RB_int = p.RB_int;
@@ -535,11 +590,17 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     e1.D_int = dbg ? dbg->DR1_int : nullptr;
     e1.final_scale = scale_needed && path_b == 0;
     if (path_a == 1) {
+      StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_spmm_valu(0, M, N, p.a_ptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, e1, st));
     } else if (path_a == 2) {
-      SRQ_HIP(h, launch_densify(p.a_ptr, p.a_idx, p.a_val, M, K, p.cap_a, p.Ad, K, st));
+      {
+        StageTimer tm(h, st, SRQ_STAGE_TERM1_PREP);
+        SRQ_HIP(h, launch_densify(p.a_ptr, p.a_idx, p.a_val, M, K, p.cap_a, p.Ad, K, st));
+      }
+      StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_gemm_i8(M, N, K, p.Ad, K, p.RB_int, K, e1, st));
     } else if (path_a == 3) {
+      StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_gemm_i8(M, N, K, p.A_int, K, p.RB_int, K, e1, st));
     }
     GemmEpilogue e2 = e1;
@@ -547,11 +608,17 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     e2.D_int = dbg ? dbg->DR2_int : nullptr;
     e2.final_scale = scale_needed;
     if (path_b == 1) {
+      StageTimer tm(h, st, SRQ_STAGE_TERM2);
       SRQ_HIP(h, launch_spmm_valu(1, N, M, p.b_ptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, e2, st));
     } else if (path_b == 2) {
-      SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, K, st));
+      {
+        StageTimer tm(h, st, SRQ_STAGE_TERM2_PREP);
+        SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, K, st));
+      }
+      StageTimer tm(h, st, SRQ_STAGE_TERM2);
       SRQ_HIP(h, launch_gemm_i8(M, N, K, p.RA_int, K, p.Bd, K, e2, st));
     } else if (path_b == 3) {
+      StageTimer tm(h, st, SRQ_STAGE_TERM2);
       SRQ_HIP(h, launch_gemm_i8(M, N, K, p.RA_int, K, p.B_int, K, e2, st));
     }
     if (scale_needed && path_a == 0 && path_b == 0) {

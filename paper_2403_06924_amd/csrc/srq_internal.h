@@ -14,6 +14,10 @@ struct srq_context {
   int last_hip_error;
   int64_t* host_nnz;     // pinned host buffer for the two counters read back in synchronising modes
   srq_intermediates_t last;
+  int prof_enabled;
+  unsigned prof_used;                       // bit i: stage i ran in the last call
+  hipEvent_t prof_ev[2 * SRQ_NUM_STAGES];   // start/stop per stage, created on enable
+  int prof_created;
 };
 
 namespace srq {
