@@ -379,8 +379,8 @@ srq_status_t srq_gemm_i8(srq_handle_t h, int64_t M, int64_t N, int64_t K, const 
   }
   SRQ_HIP(h, launch_gemm_i8(M, N, K, Qa, lda, Qb, ldb, ep, st));
   if (drow) {
-    SRQ_HIP(h, launch_reduce_means(ep.row_part, tiles(N, gemm_tile_n()), M, N, 0.f, drow, nullptr, st));
-    SRQ_HIP(h, launch_reduce_means(ep.col_part, tiles(M, gemm_tile_m()), N, M, 0.f, dcol, nullptr, st));
+    SRQ_HIP(h, launch_reduce_means(ep.row_part, gemm_tiles_n(M, N), M, N, 0.f, drow, nullptr, st));
+    SRQ_HIP(h, launch_reduce_means(ep.col_part, gemm_tiles_m(M, N), N, M, 0.f, dcol, nullptr, st));
   }
   return SRQ_STATUS_OK;
 }
@@ -523,8 +523,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     {
     StageTimer tm(h, st, SRQ_STAGE_SELECT);
     // line 7: GetAvgVec, and the thresholds of Eq. avgQuan
-    SRQ_HIP(h, launch_reduce_means(p.row_part, tiles(N, gemm_tile_n()), M, N, theta_a, p.drow, p.t_a, st));
-    SRQ_HIP(h, launch_reduce_means(p.col_part, tiles(M, gemm_tile_m()), N, M, theta_b, p.dcol, p.t_b, st));
+    SRQ_HIP(h, launch_reduce_means(p.row_part, gemm_tiles_n(M, N), M, N, theta_a, p.drow, p.t_a, st));
+    SRQ_HIP(h, launch_reduce_means(p.col_part, gemm_tiles_m(M, N), N, M, theta_b, p.dcol, p.t_b, st));
     im.drow = p.drow; im.dcol = p.dcol; im.t_a = p.t_a; im.t_b = p.t_b;
     // lines 8-10: Reduce -> CSR of A', CSC of B'
     int64_t chk = select_chunks(K);

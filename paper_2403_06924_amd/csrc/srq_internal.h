@@ -82,8 +82,10 @@ hipError_t launch_reduce_means(const double* part, int64_t nparts, int64_t nvec,
                                float theta, float* mean, float* thresh, hipStream_t st);
 
 // INT8 GEMM, both operands K-contiguous
-int gemm_tile_m();
+int gemm_tile_m();                          // smallest tile extents (upper bound on tile counts)
 int gemm_tile_n();
+int64_t gemm_tiles_m(int64_t M, int64_t N);  // tile counts of the configuration launch_gemm_i8 picks
+int64_t gemm_tiles_n(int64_t M, int64_t N);
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
                           const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st);
 
