@@ -36,6 +36,7 @@ struct Plan {
   double *row_part, *col_part;
   int32_t *cnt_a, *tot_a, *a_ptr, *cnt_b, *tot_b, *b_ptr;
   int64_t* nnz;   // [2]
+  uint64_t *mask_a, *mask_b;   // keep-bits, one row of words per vector
   int32_t *a_idx, *b_idx;
   int8_t *a_val, *b_val;
   int64_t cap_a, cap_b;
@@ -68,6 +69,8 @@ size_t plan_fixed(char* base, int64_t M, int64_t N, int64_t K, Plan* p) {
   p->cnt_b = c.take<int32_t>((size_t)chk * N); p->tot_b = c.take<int32_t>(N);
   p->b_ptr = c.take<int32_t>(N + 1);
   p->nnz = c.take<int64_t>(2);
+  p->mask_a = c.take<uint64_t>((size_t)M * mask_words(K));
+  p->mask_b = c.take<uint64_t>((size_t)N * mask_words(K));
   p->fixed_bytes = c.off;
   return c.off;
 }
@@ -478,28 +481,54 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   im.A_int = p.A_int; im.B_int = p.B_int; im.s_a = p.s_a; im.lam_a = p.lam_a; im.s_b = p.s_b; im.lam_b = p.lam_b;
 
   h->prof_used = 0;
+  const bool fastA = K > 0 && rows_fused_ok(A, K, lda, p.A_int, K, p.RA_int, K);
+  const bool fastB = K > 0 && cols_pass_ok(B, N, ldb);
+  bool ra_vm_done = false, rb_vm_done = false, rb_em_done = false;
   // lines 1: Quant.  amax per vector -> scale, lambda -> codes (and max |residual| per vector)
   {
   StageTimer tm(h, st, SRQ_STAGE_QUANTIZE);
-  SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_a), M, 0, st));
-  SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_b), N, 0, st));
-  if (comp) {
-    SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_ra), M, 0, st));
-    SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_rb), N, 0, st));
+  // operand A: vectors are contiguous rows
+  if (fastA) {
+    SRQ_HIP(h, launch_rows_fused(A, M, K, lda, qmax, trunc, p.A_int, K, p.s_a, p.lam_a,
+                                 comp ? p.RA_int : nullptr, K, p.s_ra, p.lam_ra, st));
+    ra_vm_done = comp;
+  } else {
+    SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_a), M, 0, st));
+    if (comp) SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_ra), M, 0, st));
+    SRQ_HIP(h, launch_amax(A, M, K, lda, SRQ_AXIS_ROW, reinterpret_cast<uint32_t*>(p.s_a), st));
+    SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_a), p.lam_a, M, qmax, st));
+    SRQ_HIP(h, launch_quantize_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, qmax, trunc,
+                                     SRQ_LAYOUT_VECTOR_MAJOR, p.A_int, K,
+                                     comp ? reinterpret_cast<uint32_t*>(p.s_ra) : nullptr, st));
+    if (comp) SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_ra), p.lam_ra, M, qmax, st));
   }
-  SRQ_HIP(h, launch_amax(A, M, K, lda, SRQ_AXIS_ROW, reinterpret_cast<uint32_t*>(p.s_a), st));
-  SRQ_HIP(h, launch_amax(B, K, N, ldb, SRQ_AXIS_COL, reinterpret_cast<uint32_t*>(p.s_b), st));
-  SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_a), p.lam_a, M, qmax, st));
-  SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_b), p.lam_b, N, qmax, st));
-  SRQ_HIP(h, launch_quantize_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, qmax, trunc,
-                                   SRQ_LAYOUT_VECTOR_MAJOR, p.A_int, K,
-                                   comp ? reinterpret_cast<uint32_t*>(p.s_ra) : nullptr, st));
-  SRQ_HIP(h, launch_quantize_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, qmax, trunc,
-                                   SRQ_LAYOUT_VECTOR_MAJOR, p.B_int, K,
-                                   comp ? reinterpret_cast<uint32_t*>(p.s_rb) : nullptr, st));
+  // operand B: vectors are the columns of a row-major matrix; codes are stored transposed
+  SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_b), N, 0, st));
+  if (comp) SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_rb), N, 0, st));
+  if (fastB) {
+    SRQ_HIP(h, launch_cols_amax(B, K, N, ldb, reinterpret_cast<uint32_t*>(p.s_b), st));
+    SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_b), p.lam_b, N, qmax, st));
+    SRQ_HIP(h, launch_cols_codes(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.B_int, K, nullptr, 0,
+                                 comp ? reinterpret_cast<uint32_t*>(p.s_rb) : nullptr, st));
+    if (comp) {
+      SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_rb), p.lam_rb, N, qmax, st));
+      // the K-contiguous residual codes feed the matrix-core paths; the k-major copy is only
+      // written now if the caller has fixed the vector-ALU path for term 1
+      const bool want_em = term_a && strategy == SRQ_STRATEGY_CSR_VALU && dense_fallback_density > 1.f;
+      SRQ_HIP(h, launch_cols_resid(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.lam_rb,
+                                   want_em ? nullptr : p.RB_int, K, want_em ? p.RB_em : nullptr, N, st));
+      rb_vm_done = !want_em;
+      rb_em_done = want_em;
+    }
+  } else {
+    SRQ_HIP(h, launch_amax(B, K, N, ldb, SRQ_AXIS_COL, reinterpret_cast<uint32_t*>(p.s_b), st));
+    SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_b), p.lam_b, N, qmax, st));
+    SRQ_HIP(h, launch_quantize_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, qmax, trunc,
+                                     SRQ_LAYOUT_VECTOR_MAJOR, p.B_int, K,
+                                     comp ? reinterpret_cast<uint32_t*>(p.s_rb) : nullptr, st));
+    if (comp) SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_rb), p.lam_rb, N, qmax, st));
+  }
   if (comp) {
-    SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_ra), p.lam_ra, M, qmax, st));
-    SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_rb), p.lam_rb, N, qmax, st));
     im.s_ra = p.s_ra; im.s_rb = p.s_rb;
   }
   }
@@ -529,17 +558,24 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // lines 8-10: Reduce -> CSR of A', CSC of B'
     int64_t chk = select_chunks(K);
     if (term_a) {
-      SRQ_HIP(h, launch_select_count(A, M, K, lda, SRQ_AXIS_ROW, p.t_a, p.cnt_a, st));
-      SRQ_HIP(h, launch_select_scan(p.cnt_a, M, chk, p.tot_a, p.a_ptr, p.nnz + 0, st));
-      SRQ_HIP(h, launch_select_scatter(A, M, K, lda, SRQ_AXIS_ROW, p.t_a, p.lam_a, qmax, trunc, p.a_ptr,
-                                       p.cnt_a, p.a_idx, p.a_val, p.cap_a, st));
+      // keep-bits and per-row counts, prefix scan, compaction from the mask and the codes
+      SRQ_HIP(h, launch_rows_mask(A, M, K, lda, p.t_a, p.mask_a, p.tot_a, st));
+      SRQ_HIP(h, launch_scan_totals(p.tot_a, M, p.a_ptr, p.nnz + 0, st));
+      SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, K, p.a_ptr, p.a_idx, p.a_val, p.cap_a, st));
       im.a_ptr = p.a_ptr; im.a_idx = p.a_idx; im.a_val = p.a_val; im.capacity_a = p.cap_a;
     }
     if (term_b) {
-      SRQ_HIP(h, launch_select_count(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.cnt_b, st));
-      SRQ_HIP(h, launch_select_scan(p.cnt_b, N, chk, p.tot_b, p.b_ptr, p.nnz + 1, st));
-      SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
-                                       p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));
+      if (fastB) {
+        SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.tot_b), N, 0, st));
+        SRQ_HIP(h, launch_cols_mask(B, K, N, ldb, p.t_b, p.mask_b, p.tot_b, st));
+        SRQ_HIP(h, launch_scan_totals(p.tot_b, N, p.b_ptr, p.nnz + 1, st));
+        SRQ_HIP(h, launch_scatter_mask(p.mask_b, N, K, p.B_int, K, p.b_ptr, p.b_idx, p.b_val, p.cap_b, st));
+      } else {
+        SRQ_HIP(h, launch_select_count(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.cnt_b, st));
+        SRQ_HIP(h, launch_select_scan(p.cnt_b, N, chk, p.tot_b, p.b_ptr, p.nnz + 1, st));
+        SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
+                                         p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));
+      }
       im.b_ptr = p.b_ptr; im.b_idx = p.b_idx; im.b_val = p.b_val; im.capacity_b = p.cap_b;
     }
     }
@@ -571,12 +607,21 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     bool ra_vm = path_b >= 2, ra_em = path_b == 1, rb_vm = path_a >= 2, rb_em = path_a == 1;
     {
     StageTimer tm(h, st, SRQ_STAGE_RESIDUAL);
-    if (ra_vm || ra_em)
+    // whatever the quantize stage has not already produced
+    const bool need_ra_vm = ra_vm && !ra_vm_done, need_rb_vm = rb_vm && !rb_vm_done;
+    const bool need_rb_em = rb_em && !rb_em_done;
+    if (need_ra_vm || ra_em)
       SRQ_HIP(h, launch_residual_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, p.lam_ra, qmax, trunc,
-                                       ra_vm ? p.RA_int : nullptr, K, ra_em ? p.RA_em : nullptr, M, st));
-    if (rb_vm || rb_em)
-      SRQ_HIP(h, launch_residual_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, p.lam_rb, qmax, trunc,
-                                       rb_vm ? p.RB_int : nullptr, K, rb_em ? p.RB_em : nullptr, N, st));
+                                       need_ra_vm ? p.RA_int : nullptr, K, ra_em ? p.RA_em : nullptr, M, st));
+    if (need_rb_vm || need_rb_em) {
+      if (fastB)
+        SRQ_HIP(h, launch_cols_resid(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.lam_rb,
+                                     need_rb_vm ? p.RB_int : nullptr, K, need_rb_em ? p.RB_em : nullptr, N, st));
+      else
+        SRQ_HIP(h, launch_residual_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, p.lam_rb, qmax, trunc,
+                                         need_rb_vm ? p.RB_int : nullptr, K, need_rb_em ? p.RB_em : nullptr, N,
+                                         st));
+    }
     }
     if (ra_vm) im.RA_int = p.RA_int;
     if (ra_em) im.RA_em = p.RA_em;

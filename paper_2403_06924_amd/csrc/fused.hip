@@ -1,0 +1,372 @@
+// Streaming kernels of the timed path, laid out for HBM bandwidth (Algorithm 1 lines 1, 4-6,
+// 8-10).  They compute exactly what the generic kernels in quantize.hip / select.hip compute,
+// with fewer passes over the FP32 operands:
+//
+//   rows_fused_kernel   operand A (one scale per row): the row is read ONCE into registers;
+//                       amax, lambda, codes, residual, residual amax and residual codes all
+//                       come out of that one read.
+//   cols_pass_kernel    operand B (one scale per column, row-major K x N): three streaming
+//                       passes (amax | codes + max|residual| | residual codes), each thread
+//                       holding a 16-row x 4-column patch so that the transposed (K-contiguous)
+//                       INT8 output is written 16 bytes at a time without going through LDS.
+//   *_mask_kernel       threshold compare of Eq. avgQuan -> one keep-bit per element (the only
+//                       pass that has to re-read FP32 after the first product) + per-vector
+//                       counts.
+//   scatter_mask_kernel compaction to CSR / CSC from the bit mask and the INT8 codes.
+#include "srq_internal.h"
+
+namespace srq {
+namespace {
+
+__device__ __forceinline__ int quant_code(float x, float lam, float qmax, int trunc) {
+  float y = x * lam;
+  float r = trunc ? truncf(y) : rintf(y);
+  r = fminf(fmaxf(r, -qmax), qmax);
+  return (int)r;
+}
+
+__device__ __forceinline__ float block_max_256(float m, float* sm) {
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  __syncthreads();                                   // sm may still be read from a previous use
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = m;
+  __syncthreads();
+  return fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+}
+
+__device__ __forceinline__ unsigned pack4(int a, int b, int c, int d) {
+  return (unsigned)(a & 0xff) | ((unsigned)(b & 0xff) << 8) | ((unsigned)(c & 0xff) << 16) |
+         ((unsigned)(d & 0xff) << 24);
+}
+
+// ---- operand with contiguous vectors (A): one 256-thread block per row --------------------
+template <int NV4>   // float4 pieces per thread; the row has at most 1024*NV4 elements
+__global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict__ X, int64_t cols,
+                                                         int64_t ldx, float qmax, int trunc,
+                                                         int8_t* __restrict__ Q, int64_t ldq,
+                                                         float* __restrict__ scale, float* __restrict__ lambda,
+                                                         int8_t* __restrict__ Rq, int64_t ldr,
+                                                         float* __restrict__ rscale,
+                                                         float* __restrict__ rlambda) {
+  __shared__ float sm[4];
+  const int64_t row = blockIdx.x;
+  const float4* src = reinterpret_cast<const float4*>(X + row * ldx);
+  const int64_t n4 = cols >> 2;
+  float4 x[NV4];
+  float m = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV4; ++i) {
+    int64_t c4 = threadIdx.x + i * 256;
+    x[i] = c4 < n4 ? src[c4] : make_float4(0.f, 0.f, 0.f, 0.f);
+    m = fmaxf(m, fmaxf(fmaxf(fabsf(x[i].x), fabsf(x[i].y)), fmaxf(fabsf(x[i].z), fabsf(x[i].w))));
+  }
+  const float amax = block_max_256(m, sm);
+  float lam = 0.f, s = 0.f;
+  if (amax > 0.f) { lam = qmax / amax; s = amax / qmax; }
+  unsigned* qdst = reinterpret_cast<unsigned*>(Q + row * ldq);
+  float rm = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV4; ++i) {
+    int64_t c4 = threadIdx.x + i * 256;
+    int q0 = quant_code(x[i].x, lam, qmax, trunc), q1 = quant_code(x[i].y, lam, qmax, trunc);
+    int q2 = quant_code(x[i].z, lam, qmax, trunc), q3 = quant_code(x[i].w, lam, qmax, trunc);
+    if (c4 < n4) qdst[c4] = pack4(q0, q1, q2, q3);
+    if (Rq) {
+      // residual r = fl(x - fl(float(q) * s)); kept in place of x
+      x[i].x = x[i].x - (float)q0 * s; x[i].y = x[i].y - (float)q1 * s;
+      x[i].z = x[i].z - (float)q2 * s; x[i].w = x[i].w - (float)q3 * s;
+      rm = fmaxf(rm, fmaxf(fmaxf(fabsf(x[i].x), fabsf(x[i].y)), fmaxf(fabsf(x[i].z), fabsf(x[i].w))));
+    }
+  }
+  if (threadIdx.x == 0) { scale[row] = s; lambda[row] = lam; }
+  if (!Rq) return;
+  const float ramax = block_max_256(rm, sm);
+  float rlam = 0.f, rs = 0.f;
+  if (ramax > 0.f) { rlam = qmax / ramax; rs = ramax / qmax; }
+  unsigned* rdst = reinterpret_cast<unsigned*>(Rq + row * ldr);
+#pragma unroll
+  for (int i = 0; i < NV4; ++i) {
+    int64_t c4 = threadIdx.x + i * 256;
+    if (c4 < n4)
+      rdst[c4] = pack4(quant_code(x[i].x, rlam, qmax, trunc), quant_code(x[i].y, rlam, qmax, trunc),
+                       quant_code(x[i].z, rlam, qmax, trunc), quant_code(x[i].w, rlam, qmax, trunc));
+  }
+  if (threadIdx.x == 0) { rscale[row] = rs; rlambda[row] = rlam; }
+}
+
+// ---- operand with strided vectors (B, columns of a row-major matrix) ------------------------
+// A block covers 256 rows x 64 columns; thread (cg, rb) holds rows rb*16..rb*16+15 of the four
+// columns cg*4..cg*4+3.
+enum ColsMode { kColsAmax = 0, kColsCodes = 1, kColsResid = 2, kColsMask = 3 };
+
+template <int MODE>
+__global__ __launch_bounds__(256) void cols_pass_kernel(
+    const float* __restrict__ X, int64_t rows, int64_t cols, int64_t ldx, float qmax, int trunc,
+    const float* __restrict__ scale, const float* __restrict__ lambda, const float* __restrict__ rlambda,
+    const float* __restrict__ thresh, uint32_t* __restrict__ amax_bits,   // amax or residual amax (bits)
+    int8_t* __restrict__ Qvm, int64_t ldvm,      // transposed output [col][row], may be null
+    int8_t* __restrict__ Qem, int64_t ldem,      // straight output [row][col], may be null
+    uint8_t* __restrict__ mask, int64_t mask_stride,   // bytes per column of the transposed bit mask
+    int32_t* __restrict__ counts) {
+  __shared__ uint32_t red[64];
+  const int cg = threadIdx.x & 15, rb = threadIdx.x >> 4;
+  const int64_t col0 = (int64_t)blockIdx.x * 64 + cg * 4;
+  const int64_t row0 = (int64_t)blockIdx.y * 256 + rb * 16;
+  const bool colok = col0 < cols;                 // cols is a multiple of 4
+  if (MODE != kColsResid) {
+    if (threadIdx.x < 64) red[threadIdx.x] = 0;
+    __syncthreads();
+  }
+  float4 v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    int64_t r = row0 + i;
+    v[i] = (colok && r < rows) ? *reinterpret_cast<const float4*>(X + r * ldx + col0)
+                               : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  if (MODE == kColsAmax) {
+    float m[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      m[0] = fmaxf(m[0], fabsf(v[i].x)); m[1] = fmaxf(m[1], fabsf(v[i].y));
+      m[2] = fmaxf(m[2], fabsf(v[i].z)); m[3] = fmaxf(m[3], fabsf(v[i].w));
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) atomicMax(&red[cg * 4 + c], __float_as_uint(m[c]));
+    __syncthreads();
+    if (threadIdx.x < 64) {
+      int64_t col = (int64_t)blockIdx.x * 64 + threadIdx.x;
+      if (col < cols) atomicMax(&amax_bits[col], red[threadIdx.x]);
+    }
+    return;
+  }
+  if (MODE == kColsMask) {
+    float4 t = colok ? *reinterpret_cast<const float4*>(thresh + col0) : make_float4(0.f, 0.f, 0.f, 0.f);
+    const float tt[4] = {t.x, t.y, t.z, t.w};
+    unsigned bits[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      bool ok = colok && row0 + i < rows;
+      const float xv[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) bits[c] |= (ok && fabsf(xv[c]) > tt[c]) ? (1u << i) : 0u;
+    }
+    if (colok && row0 < mask_stride * 8) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        *reinterpret_cast<uint16_t*>(mask + (col0 + c) * mask_stride + (row0 >> 3)) = (uint16_t)bits[c];
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (bits[c]) atomicAdd(&red[cg * 4 + c], (uint32_t)__popc(bits[c]));
+    __syncthreads();
+    if (threadIdx.x < 64) {
+      int64_t col = (int64_t)blockIdx.x * 64 + threadIdx.x;
+      if (col < cols && red[threadIdx.x]) atomicAdd(&counts[col], (int32_t)red[threadIdx.x]);
+    }
+    return;
+  }
+  // codes / residual codes
+  float4 l4 = colok ? *reinterpret_cast<const float4*>(lambda + col0) : make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 s4 = colok ? *reinterpret_cast<const float4*>(scale + col0) : make_float4(0.f, 0.f, 0.f, 0.f);
+  const float lam[4] = {l4.x, l4.y, l4.z, l4.w}, sc[4] = {s4.x, s4.y, s4.z, s4.w};
+  float rlam[4] = {0.f, 0.f, 0.f, 0.f};
+  if (MODE == kColsResid && colok) {
+    float4 r4 = *reinterpret_cast<const float4*>(rlambda + col0);
+    rlam[0] = r4.x; rlam[1] = r4.y; rlam[2] = r4.z; rlam[3] = r4.w;
+  }
+  float rm[4] = {0.f, 0.f, 0.f, 0.f};
+  unsigned packed[4][4];                            // [column][word]: 16 codes of one column
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int wd = 0; wd < 4; ++wd) packed[c][wd] = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const float xv[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+    int code[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      int q = quant_code(xv[c], lam[c], qmax, trunc);
+      float res = xv[c] - (float)q * sc[c];
+      if (MODE == kColsCodes) {
+        code[c] = q;
+        rm[c] = fmaxf(rm[c], fabsf(res));
+      } else {
+        code[c] = quant_code(res, rlam[c], qmax, trunc);
+      }
+      packed[c][i >> 2] |= (unsigned)(code[c] & 0xff) << (8 * (i & 3));
+    }
+    if (Qem && colok && row0 + i < rows)
+      *reinterpret_cast<unsigned*>(Qem + (row0 + i) * ldem + col0) = pack4(code[0], code[1], code[2], code[3]);
+  }
+  if (Qvm && colok && row0 < rows) {
+    const bool full = row0 + 16 <= rows;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      int8_t* dst = Qvm + (col0 + c) * ldvm + row0;
+      if (full) {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(packed[c][0], packed[c][1], packed[c][2], packed[c][3]);
+      } else {
+        for (int i = 0; i < 16; ++i)
+          if (row0 + i < rows) dst[i] = (int8_t)((packed[c][i >> 2] >> (8 * (i & 3))) & 0xff);
+      }
+    }
+  }
+  if (MODE == kColsCodes && amax_bits) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) atomicMax(&red[cg * 4 + c], __float_as_uint(rm[c]));
+    __syncthreads();
+    if (threadIdx.x < 64) {
+      int64_t col = (int64_t)blockIdx.x * 64 + threadIdx.x;
+      if (col < cols) atomicMax(&amax_bits[col], red[threadIdx.x]);
+    }
+  }
+}
+
+// ---- keep-mask of an operand with contiguous vectors (A): one block per row ------------------
+__global__ __launch_bounds__(256) void rows_mask_kernel(const float* __restrict__ X, int64_t cols, int64_t ldx,
+                                                        const float* __restrict__ thresh,
+                                                        uint64_t* __restrict__ mask, int64_t words,
+                                                        int32_t* __restrict__ counts) {
+  __shared__ int sm[4];
+  const int64_t row = blockIdx.x;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const float t = thresh[row];
+  const float* src = X + row * ldx;
+  int total = 0;
+  for (int64_t wd = w; wd < words; wd += 4) {
+    int64_t e = wd * 64 + lane;
+    bool keep = e < cols && fabsf(src[e]) > t;
+    unsigned long long m = __ballot(keep);
+    if (lane == 0) mask[row * words + wd] = m;
+    total += __popcll(m);
+  }
+  if (lane == 0) sm[w] = total;
+  __syncthreads();
+  if (threadIdx.x == 0) counts[row] = sm[0] + sm[1] + sm[2] + sm[3];
+}
+
+// ---- compaction: one block per vector, each wave a contiguous quarter of its mask words --------
+__global__ __launch_bounds__(256) void scatter_mask_kernel(const uint64_t* __restrict__ mask, int64_t words,
+                                                           const int8_t* __restrict__ Q, int64_t ldq,
+                                                           const int32_t* __restrict__ ptr,
+                                                           int32_t* __restrict__ idx, int8_t* __restrict__ val,
+                                                           int64_t capacity) {
+  const int64_t v = blockIdx.x;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const uint64_t* mv = mask + v * words;
+  const int64_t per = (words + 3) / 4;
+  const int64_t w0 = w * per, w1 = w0 + per < words ? w0 + per : words;
+  // kept entries in the words before this wave's range
+  int before = 0;
+  for (int64_t i = lane; i < w0 && i < words; i += 64) before += __popcll(mv[i]);
+  for (int off = 32; off > 0; off >>= 1) before += __shfl_xor(before, off, 64);
+  int64_t base = (int64_t)ptr[v] + before;
+  const int8_t* qv = Q + v * ldq;
+  for (int64_t wd = w0; wd < w1; ++wd) {
+    unsigned long long m = mv[wd];
+    if (m == 0) continue;
+    if ((m >> lane) & 1ull) {
+      int64_t pos = base + __popcll(m & ((1ull << lane) - 1ull));
+      int64_t e = wd * 64 + lane;
+      if (pos < capacity) {
+        idx[pos] = (int32_t)e;
+        val[pos] = qv[e];
+      }
+    }
+    base += __popcll(m);
+  }
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+bool rows_fused_ok(const float* X, int64_t cols, int64_t ldx, const int8_t* Q, int64_t ldq, const int8_t* Rq,
+                   int64_t ldr) {
+  return cols > 0 && cols <= 16384 && (cols % 4) == 0 && (ldx % 4) == 0 && aligned16(X) && (ldq % 4) == 0 &&
+         aligned16(Q) && (!Rq || ((ldr % 4) == 0 && aligned16(Rq)));
+}
+
+hipError_t launch_rows_fused(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                             int8_t* Q, int64_t ldq, float* scale, float* lambda, int8_t* Rq, int64_t ldr,
+                             float* rscale, float* rlambda, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  dim3 grid((unsigned)rows), block(256);
+  const float qm = (float)qmax;
+#define SRQ_ROWS(NV4)                                                                                        \
+  hipLaunchKernelGGL(rows_fused_kernel<NV4>, grid, block, 0, st, X, cols, ldx, qm, trunc, Q, ldq, scale,     \
+                     lambda, Rq, ldr, rscale, rlambda)
+  if (cols <= 1024) SRQ_ROWS(1);
+  else if (cols <= 2048) SRQ_ROWS(2);
+  else if (cols <= 4096) SRQ_ROWS(4);
+  else if (cols <= 8192) SRQ_ROWS(8);
+  else SRQ_ROWS(16);
+#undef SRQ_ROWS
+  return hipGetLastError();
+}
+
+bool cols_pass_ok(const float* X, int64_t cols, int64_t ldx) {
+  return cols > 0 && (cols % 4) == 0 && (ldx % 4) == 0 && aligned16(X);
+}
+
+static dim3 cols_grid(int64_t rows, int64_t cols) {
+  return dim3((unsigned)((cols + 63) / 64), (unsigned)((rows + 255) / 256));
+}
+
+hipError_t launch_cols_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, uint32_t* amax_bits,
+                            hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  hipLaunchKernelGGL(cols_pass_kernel<kColsAmax>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+                     0.f, 0, nullptr, nullptr, nullptr, nullptr, amax_bits, nullptr, 0, nullptr, 0, nullptr, 0,
+                     nullptr);
+  return hipGetLastError();
+}
+
+hipError_t launch_cols_codes(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                             const float* scale, const float* lambda, int8_t* Qvm, int64_t ldvm, int8_t* Qem,
+                             int64_t ldem, uint32_t* ramax_bits, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  hipLaunchKernelGGL(cols_pass_kernel<kColsCodes>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+                     (float)qmax, trunc, scale, lambda, nullptr, nullptr, ramax_bits, Qvm, ldvm, Qem, ldem,
+                     nullptr, 0, nullptr);
+  return hipGetLastError();
+}
+
+hipError_t launch_cols_resid(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                             const float* scale, const float* lambda, const float* rlambda, int8_t* Rvm,
+                             int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st) {
+  if (rows <= 0 || cols <= 0 || (!Rvm && !Rem)) return hipSuccess;
+  hipLaunchKernelGGL(cols_pass_kernel<kColsResid>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+                     (float)qmax, trunc, scale, lambda, rlambda, nullptr, nullptr, Rvm, ldvm, Rem, ldem, nullptr,
+                     0, nullptr);
+  return hipGetLastError();
+}
+
+// counts[cols] must be zero on entry; mask holds mask_words(rows) 64-bit words per column
+hipError_t launch_cols_mask(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* thresh,
+                            uint64_t* mask, int32_t* counts, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  hipLaunchKernelGGL(cols_pass_kernel<kColsMask>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+                     0.f, 0, nullptr, nullptr, nullptr, thresh, nullptr, nullptr, 0, nullptr, 0,
+                     reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts);
+  return hipGetLastError();
+}
+
+hipError_t launch_rows_mask(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* thresh,
+                            uint64_t* mask, int32_t* counts, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(rows_mask_kernel, dim3((unsigned)rows), dim3(256), 0, st, X, cols, ldx, thresh, mask,
+                     mask_words(cols), counts);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter_mask(const uint64_t* mask, int64_t nvec, int64_t veclen, const int8_t* Q, int64_t ldq,
+                               const int32_t* ptr, int32_t* idx, int8_t* val, int64_t capacity, hipStream_t st) {
+  if (nvec <= 0 || veclen <= 0) return hipSuccess;
+  hipLaunchKernelGGL(scatter_mask_kernel, dim3((unsigned)nvec), dim3(256), 0, st, mask, mask_words(veclen), Q,
+                     ldq, ptr, idx, val, capacity);
+  return hipGetLastError();
+}
+
+}  // namespace srq

@@ -12,8 +12,6 @@
 // global -> registers -> LDS, double buffered so that the loads of step t+1 are in flight
 // while step t is multiplied.  LDS rows are padded by 16 bytes so the 16-byte fragment reads
 // of 16 consecutive rows fall on distinct banks.
-#include <stdlib.h>
-
 #include "srq_internal.h"
 
 namespace srq {
@@ -62,7 +60,7 @@ template <int BM, int BN, int BK, bool FAST, bool DBG>
 __global__ __launch_bounds__(256) void gemm_i8_kernel(int64_t M, int64_t N, int64_t K,
                                                       const int8_t* __restrict__ Qa, int64_t lda,
                                                       const int8_t* __restrict__ Qb, int64_t ldb,
-                                                      int64_t tiles_m, int64_t tiles_n, int variant,
+                                                      int64_t tiles_m, int64_t tiles_n,
                                                       GemmEpilogue ep) {
   using C = Cfg<BM, BN, BK>;
   extern __shared__ __attribute__((aligned(16))) int8_t lds[];
@@ -76,12 +74,12 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(int64_t M, int64_t N, int6
   const int64_t total = tiles_m * tiles_n;
   {
     const int64_t per = total / 8;
-    if (!(variant & 1) && per > 0 && bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
+    if (per > 0 && bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
   }
   // within the band, walk the tiles in groups of 8 rows (column-major inside a group)
   int64_t tile_m, tile_n;
   {
-    const int64_t g = (variant & 4) ? 4 : ((variant & 8) ? 16 : 8);
+    const int64_t g = 8;
     int64_t grp = bid / (g * tiles_n);
     int64_t first = grp * g;
     int64_t rows_in = tiles_m - first < g ? tiles_m - first : g;
@@ -327,7 +325,7 @@ __global__ void scale_only_kernel(int64_t M, int64_t N, GemmEpilogue ep) {
 
 template <int BM, int BN, int BK>
 hipError_t launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb,
-                      int64_t ldb, const GemmEpilogue& ep, bool fast, int variant, hipStream_t st) {
+                      int64_t ldb, const GemmEpilogue& ep, bool fast, hipStream_t st) {
   using C = Cfg<BM, BN, BK>;
   int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
   dim3 grid((unsigned)(tm * tn));
@@ -347,7 +345,7 @@ hipError_t launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t
     if (e != hipSuccess) return e;
     attr_done[slot] = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds_bytes, st, M, N, K, Qa, lda, Qb, ldb, tm, tn, variant, ep);
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds_bytes, st, M, N, K, Qa, lda, Qb, ldb, tm, tn, ep);
   return hipGetLastError();
 }
 
@@ -369,13 +367,11 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int
   // fast path: every 16-byte piece is aligned and inside [0,K)
   bool fast = ((reinterpret_cast<uintptr_t>(Qa) | reinterpret_cast<uintptr_t>(Qb)) & 15) == 0 &&
               (lda % 16) == 0 && (ldb % 16) == 0 && K > 0 && (K % 64) == 0;
-  static int variant = -1;
-  if (variant < 0) { const char* e = getenv("SRQ_GEMM_VARIANT"); variant = e ? atoi(e) : 0; }
   if (use_big_tiles(M, N)) {
-    if (!(variant & 2) && fast && K % 128 == 0) return launch_cfg<256, 256, 128>(M, N, K, Qa, lda, Qb, ldb, ep, fast, variant, st);
-    return launch_cfg<256, 256, 64>(M, N, K, Qa, lda, Qb, ldb, ep, fast, variant, st);
+    if (fast && K % 128 == 0) return launch_cfg<256, 256, 128>(M, N, K, Qa, lda, Qb, ldb, ep, fast, st);
+    return launch_cfg<256, 256, 64>(M, N, K, Qa, lda, Qb, ldb, ep, fast, st);
   }
-  return launch_cfg<128, 128, 64>(M, N, K, Qa, lda, Qb, ldb, ep, fast, variant, st);
+  return launch_cfg<128, 128, 64>(M, N, K, Qa, lda, Qb, ldb, ep, fast, st);
 }
 
 hipError_t launch_scale_only(int64_t M, int64_t N, const GemmEpilogue& ep, hipStream_t st) {

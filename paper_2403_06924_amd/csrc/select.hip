@@ -224,6 +224,12 @@ hipError_t launch_select_scan(int32_t* cnt_then_off, int64_t nvec, int64_t nchun
   return hipGetLastError();
 }
 
+hipError_t launch_scan_totals(const int32_t* totals, int64_t nvec, int32_t* ptr, int64_t* nnz_dev,
+                              hipStream_t st) {
+  hipLaunchKernelGGL(scan_totals_kernel, dim3(1), dim3(1024), 0, st, totals, nvec, ptr, nnz_dev);
+  return hipGetLastError();
+}
+
 hipError_t launch_select_scatter(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
                                  const float* thresh, const float* lambda, int qmax, int trunc,
                                  const int32_t* ptr, const int32_t* off, int32_t* idx, int8_t* val,

@@ -76,6 +76,32 @@ hipError_t launch_select_scatter(const float* X, int64_t rows, int64_t cols, int
                                  const int32_t* ptr, const int32_t* off, int32_t* idx, int8_t* val,
                                  int64_t capacity, hipStream_t st);
 inline int64_t select_chunks(int64_t veclen) { return (veclen + kSelChunk - 1) / kSelChunk; }
+// exclusive scan of per-vector totals into ptr[nvec+1]; *nnz_dev = grand total
+hipError_t launch_scan_totals(const int32_t* totals, int64_t nvec, int32_t* ptr, int64_t* nnz_dev,
+                              hipStream_t st);
+
+// ---- streaming fast paths (fused.hip); the *_ok predicates say whether shapes/alignment allow them
+inline int64_t mask_words(int64_t veclen) { return (veclen + 63) / 64; }
+bool rows_fused_ok(const float* X, int64_t cols, int64_t ldx, const int8_t* Q, int64_t ldq, const int8_t* Rq,
+                   int64_t ldr);
+hipError_t launch_rows_fused(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                             int8_t* Q, int64_t ldq, float* scale, float* lambda, int8_t* Rq, int64_t ldr,
+                             float* rscale, float* rlambda, hipStream_t st);
+bool cols_pass_ok(const float* X, int64_t cols, int64_t ldx);
+hipError_t launch_cols_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, uint32_t* amax_bits,
+                            hipStream_t st);
+hipError_t launch_cols_codes(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                             const float* scale, const float* lambda, int8_t* Qvm, int64_t ldvm, int8_t* Qem,
+                             int64_t ldem, uint32_t* ramax_bits, hipStream_t st);
+hipError_t launch_cols_resid(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                             const float* scale, const float* lambda, const float* rlambda, int8_t* Rvm,
+                             int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st);
+hipError_t launch_cols_mask(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* thresh,
+                            uint64_t* mask, int32_t* counts, hipStream_t st);
+hipError_t launch_rows_mask(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* thresh,
+                            uint64_t* mask, int32_t* counts, hipStream_t st);
+hipError_t launch_scatter_mask(const uint64_t* mask, int64_t nvec, int64_t veclen, const int8_t* Q, int64_t ldq,
+                               const int32_t* ptr, int32_t* idx, int8_t* val, int64_t capacity, hipStream_t st);
 
 // thresholds from the partial sums of the GEMM epilogue
 hipError_t launch_reduce_means(const double* part, int64_t nparts, int64_t nvec, int64_t count,
