@@ -555,30 +555,20 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     SRQ_HIP(h, launch_reduce_means(p.row_part, gemm_tiles_n(M, N), M, N, theta_a, p.drow, p.t_a, st));
     SRQ_HIP(h, launch_reduce_means(p.col_part, gemm_tiles_m(M, N), N, M, theta_b, p.dcol, p.t_b, st));
     im.drow = p.drow; im.dcol = p.dcol; im.t_a = p.t_a; im.t_b = p.t_b;
-    // lines 8-10: Reduce -> CSR of A', CSC of B'
+    // lines 8-10: Reduce.  Keep-bits and per-vector counts, then the prefix scans
     int64_t chk = select_chunks(K);
-    if (term_a) {
-      // keep-bits and per-row counts, prefix scan, compaction from the mask and the codes
-      SRQ_HIP(h, launch_rows_mask(A, M, K, lda, p.t_a, p.mask_a, p.tot_a, st));
-      SRQ_HIP(h, launch_scan_totals(p.tot_a, M, p.a_ptr, p.nnz + 0, st));
-      SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, K, p.a_ptr, p.a_idx, p.a_val, p.cap_a, st));
-      im.a_ptr = p.a_ptr; im.a_idx = p.a_idx; im.a_val = p.a_val; im.capacity_a = p.cap_a;
-    }
+    if (term_a) SRQ_HIP(h, launch_rows_mask(A, M, K, lda, p.t_a, p.mask_a, p.tot_a, st));
     if (term_b) {
       if (fastB) {
         SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.tot_b), N, 0, st));
         SRQ_HIP(h, launch_cols_mask(B, K, N, ldb, p.t_b, p.mask_b, p.tot_b, st));
-        SRQ_HIP(h, launch_scan_totals(p.tot_b, N, p.b_ptr, p.nnz + 1, st));
-        SRQ_HIP(h, launch_scatter_mask(p.mask_b, N, K, p.B_int, K, p.b_ptr, p.b_idx, p.b_val, p.cap_b, st));
       } else {
         SRQ_HIP(h, launch_select_count(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.cnt_b, st));
         SRQ_HIP(h, launch_select_scan(p.cnt_b, N, chk, p.tot_b, p.b_ptr, p.nnz + 1, st));
-        SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
-                                         p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));
       }
-      im.b_ptr = p.b_ptr; im.b_idx = p.b_idx; im.b_val = p.b_val; im.capacity_b = p.cap_b;
     }
-    }
+    SRQ_HIP(h, launch_scan_pair(term_a ? p.tot_a : nullptr, M, p.a_ptr, p.nnz + 0,
+                                (term_b && fastB) ? p.tot_b : nullptr, N, p.b_ptr, p.nnz + 1, st));
     // line 9 and the branch of line 11: which execution each term takes
     const bool sync_mode = strategy == SRQ_STRATEGY_AUTO || dense_fallback_density <= 1.f;
     if (sync_mode) {
@@ -601,6 +591,25 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     } else {
       if (term_a) path_a = (int)strategy;
       if (term_b) path_b = (int)strategy;
+    }
+    // compaction to CSR of A' / CSC of B'; a term that will run on the matrix cores also gets
+    // its operand expanded to zero-filled dense codes in the same pass
+    if (term_a) {
+      SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, K, p.a_ptr, p.a_idx, p.a_val, p.cap_a,
+                                     path_a == 2 ? p.Ad : nullptr, K, st));
+      im.a_ptr = p.a_ptr; im.a_idx = p.a_idx; im.a_val = p.a_val; im.capacity_a = p.cap_a;
+    }
+    if (term_b) {
+      if (fastB) {
+        SRQ_HIP(h, launch_scatter_mask(p.mask_b, N, K, p.B_int, K, p.b_ptr, p.b_idx, p.b_val, p.cap_b,
+                                       path_b == 2 ? p.Bd : nullptr, K, st));
+      } else {
+        SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
+                                         p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));
+        if (path_b == 2) SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, K, st));
+      }
+      im.b_ptr = p.b_ptr; im.b_idx = p.b_idx; im.b_val = p.b_val; im.capacity_b = p.cap_b;
+    }
     }
     // lines 4-6: residual matrices and their codes, in the layouts the chosen paths read
     // (RA feeds term 2, RB feeds term 1)
@@ -638,10 +647,6 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_spmm_valu(0, M, N, p.a_ptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, e1, st));
     } else if (path_a == 2) {
-      {
-        StageTimer tm(h, st, SRQ_STAGE_TERM1_PREP);
-        SRQ_HIP(h, launch_densify(p.a_ptr, p.a_idx, p.a_val, M, K, p.cap_a, p.Ad, K, st));
-      }
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_gemm_i8(M, N, K, p.Ad, K, p.RB_int, K, e1, st));
     } else if (path_a == 3) {
@@ -656,10 +661,6 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
       SRQ_HIP(h, launch_spmm_valu(1, N, M, p.b_ptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, e2, st));
     } else if (path_b == 2) {
-      {
-        StageTimer tm(h, st, SRQ_STAGE_TERM2_PREP);
-        SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, K, st));
-      }
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
       SRQ_HIP(h, launch_gemm_i8(M, N, K, p.RA_int, K, p.Bd, K, e2, st));
     } else if (path_b == 3) {

@@ -224,6 +224,7 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
 }
 
 // ---- keep-mask of an operand with contiguous vectors (A): one block per row ------------------
+// Generic version: one 64-bit word per wave iteration via ballot.
 __global__ __launch_bounds__(256) void rows_mask_kernel(const float* __restrict__ X, int64_t cols, int64_t ldx,
                                                         const float* __restrict__ thresh,
                                                         uint64_t* __restrict__ mask, int64_t words,
@@ -246,35 +247,143 @@ __global__ __launch_bounds__(256) void rows_mask_kernel(const float* __restrict_
   if (threadIdx.x == 0) counts[row] = sm[0] + sm[1] + sm[2] + sm[3];
 }
 
-// ---- compaction: one block per vector, each wave a contiguous quarter of its mask words --------
+// Streaming version (16-byte aligned rows of at most 1024*NV4 elements): every thread has all
+// of its float4 loads in flight at once; two neighbouring threads make one mask byte.
+template <int NV4>
+__global__ __launch_bounds__(256) void rows_mask_vec_kernel(const float* __restrict__ X, int64_t cols, int64_t ldx,
+                                                            const float* __restrict__ thresh,
+                                                            uint8_t* __restrict__ mask, int64_t mask_stride,
+                                                            int32_t* __restrict__ counts) {
+  __shared__ int sm[4];
+  const int64_t row = blockIdx.x;
+  const float t = thresh[row];
+  const float4* src = reinterpret_cast<const float4*>(X + row * ldx);
+  const int64_t n4 = cols >> 2;
+  float4 x[NV4];
+#pragma unroll
+  for (int i = 0; i < NV4; ++i) {
+    int64_t c4 = threadIdx.x + i * 256;
+    x[i] = c4 < n4 ? src[c4] : make_float4(0.f, 0.f, 0.f, 0.f);   // |0| > t is false for every t >= 0
+  }
+  uint8_t* mrow = mask + row * mask_stride;
+  int total = 0;
+#pragma unroll
+  for (int i = 0; i < NV4; ++i) {
+    int64_t c4 = threadIdx.x + i * 256;
+    unsigned nib = (fabsf(x[i].x) > t ? 1u : 0u) | (fabsf(x[i].y) > t ? 2u : 0u) |
+                   (fabsf(x[i].z) > t ? 4u : 0u) | (fabsf(x[i].w) > t ? 8u : 0u);
+    if (c4 >= n4) nib = 0;
+    total += __popc(nib);
+    unsigned hi = __shfl_down(nib, 1, 64);
+    if (!(threadIdx.x & 1) && (c4 >> 1) < mask_stride) mrow[c4 >> 1] = (uint8_t)(nib | (hi << 4));
+  }
+  for (int off = 32; off > 0; off >>= 1) total += __shfl_xor(total, off, 64);
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = total;
+  __syncthreads();
+  if (threadIdx.x == 0) counts[row] = sm[0] + sm[1] + sm[2] + sm[3];
+}
+
+// ---- compaction: one block per vector; a thread owns whole mask words and walks their set bits.
+// Optionally also writes the vector expanded to zero-filled dense codes (operand of the
+// matrix-core execution of the sparse product).
 __global__ __launch_bounds__(256) void scatter_mask_kernel(const uint64_t* __restrict__ mask, int64_t words,
-                                                           const int8_t* __restrict__ Q, int64_t ldq,
-                                                           const int32_t* __restrict__ ptr,
+                                                           int64_t veclen, const int8_t* __restrict__ Q,
+                                                           int64_t ldq, const int32_t* __restrict__ ptr,
                                                            int32_t* __restrict__ idx, int8_t* __restrict__ val,
-                                                           int64_t capacity) {
+                                                           int64_t capacity, int8_t* __restrict__ dense,
+                                                           int64_t ldd) {
+  __shared__ int wsum[4];
   const int64_t v = blockIdx.x;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const uint64_t* mv = mask + v * words;
-  const int64_t per = (words + 3) / 4;
-  const int64_t w0 = w * per, w1 = w0 + per < words ? w0 + per : words;
-  // kept entries in the words before this wave's range
-  int before = 0;
-  for (int64_t i = lane; i < w0 && i < words; i += 64) before += __popcll(mv[i]);
-  for (int off = 32; off > 0; off >>= 1) before += __shfl_xor(before, off, 64);
-  int64_t base = (int64_t)ptr[v] + before;
   const int8_t* qv = Q + v * ldq;
-  for (int64_t wd = w0; wd < w1; ++wd) {
-    unsigned long long m = mv[wd];
-    if (m == 0) continue;
-    if ((m >> lane) & 1ull) {
-      int64_t pos = base + __popcll(m & ((1ull << lane) - 1ull));
-      int64_t e = wd * 64 + lane;
+  if (dense) {
+    // dense[e] = kept ? code : 0, eight codes (one mask byte) per step
+    int8_t* dv = dense + v * ldd;
+    const uint8_t* mb = reinterpret_cast<const uint8_t*>(mv);
+    const bool vec = ((reinterpret_cast<uintptr_t>(qv) | reinterpret_cast<uintptr_t>(dv)) & 7) == 0;
+    const int64_t n8 = veclen >> 3;
+    for (int64_t i = tid; i < n8; i += 256) {
+      unsigned bits = mb[i];
+      if (vec) {
+        uint2 c = *reinterpret_cast<const uint2*>(qv + i * 8);
+        unsigned lo = 0, hi = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          lo |= (bits >> b & 1u) ? (0xffu << (8 * b)) : 0u;
+          hi |= (bits >> (b + 4) & 1u) ? (0xffu << (8 * b)) : 0u;
+        }
+        *reinterpret_cast<uint2*>(dv + i * 8) = make_uint2(c.x & lo, c.y & hi);
+      } else {
+        for (int b = 0; b < 8; ++b) dv[i * 8 + b] = (bits >> b & 1u) ? qv[i * 8 + b] : (int8_t)0;
+      }
+    }
+    for (int64_t e = n8 * 8 + tid; e < veclen; e += 256)
+      dv[e] = (mb[e >> 3] >> (e & 7) & 1u) ? qv[e] : (int8_t)0;
+  }
+  // words [t*per, (t+1)*per) belong to thread t; exclusive prefix of their popcounts
+  const int64_t per = (words + 255) / 256;
+  const int64_t w0 = (int64_t)tid * per, w1 = w0 + per < words ? w0 + per : words;
+  int mine = 0;
+  for (int64_t i = w0; i < w1; ++i) mine += __popcll(mv[i]);
+  int inc = mine;
+  for (int d = 1; d < 64; d <<= 1) {
+    int y = __shfl_up(inc, d, 64);
+    if (lane >= d) inc += y;
+  }
+  if (lane == 63) wsum[w] = inc;
+  __syncthreads();
+  int64_t pos = (int64_t)ptr[v] + (inc - mine);
+  for (int i = 0; i < w; ++i) pos += wsum[i];
+  for (int64_t i = w0; i < w1; ++i) {
+    unsigned long long m = mv[i];
+    while (m) {
+      int bit = __ffsll((long long)m) - 1;
+      m &= m - 1;
+      int64_t e = i * 64 + bit;
       if (pos < capacity) {
         idx[pos] = (int32_t)e;
         val[pos] = qv[e];
       }
+      ++pos;
     }
-    base += __popcll(m);
+  }
+}
+
+// exclusive scans of two count vectors in one launch (block 0: first, block 1: second)
+__global__ __launch_bounds__(1024) void scan_pair_kernel(const int32_t* t0, int64_t n0, int32_t* p0, int64_t* z0,
+                                                         const int32_t* t1, int64_t n1, int32_t* p1, int64_t* z1) {
+  const int32_t* totals = blockIdx.x == 0 ? t0 : t1;
+  const int64_t nvec = blockIdx.x == 0 ? n0 : n1;
+  int32_t* ptr = blockIdx.x == 0 ? p0 : p1;
+  int64_t* nnz_dev = blockIdx.x == 0 ? z0 : z1;
+  if (!totals) return;
+  __shared__ int64_t wave_sum[16];
+  __shared__ int64_t carry_s;
+  int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  for (int64_t base = 0; base < nvec; base += 1024) {
+    int64_t v = base + tid;
+    int64_t x = v < nvec ? totals[v] : 0;
+    int64_t inc = x;
+    for (int d = 1; d < 64; d <<= 1) {
+      int64_t y = __shfl_up(inc, d, 64);
+      if (lane >= d) inc += y;
+    }
+    if (lane == 63) wave_sum[w] = inc;
+    __syncthreads();
+    int64_t wave_off = 0;
+    for (int i = 0; i < w; ++i) wave_off += wave_sum[i];
+    int64_t carry = carry_s;
+    if (v < nvec) ptr[v] = (int32_t)(carry + wave_off + inc - x);
+    __syncthreads();
+    if (tid == 1023) carry_s = carry + wave_off + inc;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    ptr[nvec] = (int32_t)carry_s;
+    if (nnz_dev) *nnz_dev = carry_s;
   }
 }
 
@@ -356,16 +465,40 @@ hipError_t launch_cols_mask(const float* X, int64_t rows, int64_t cols, int64_t 
 hipError_t launch_rows_mask(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* thresh,
                             uint64_t* mask, int32_t* counts, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(rows_mask_kernel, dim3((unsigned)rows), dim3(256), 0, st, X, cols, ldx, thresh, mask,
-                     mask_words(cols), counts);
+  const int64_t words = mask_words(cols);
+  dim3 grid((unsigned)rows), block(256);
+  if (cols > 0 && cols <= 16384 && (cols % 4) == 0 && (ldx % 4) == 0 && aligned16(X)) {
+    uint8_t* mb = reinterpret_cast<uint8_t*>(mask);
+#define SRQ_MASK(NV4)                                                                                     \
+  hipLaunchKernelGGL(rows_mask_vec_kernel<NV4>, grid, block, 0, st, X, cols, ldx, thresh, mb, words * 8, counts)
+    // the last word of a row is written in full only when cols is a multiple of 64; otherwise
+    // the generic kernel, which writes whole words, is used
+    if ((cols % 64) == 0) {
+      if (cols <= 1024) SRQ_MASK(1);
+      else if (cols <= 2048) SRQ_MASK(2);
+      else if (cols <= 4096) SRQ_MASK(4);
+      else if (cols <= 8192) SRQ_MASK(8);
+      else SRQ_MASK(16);
+      return hipGetLastError();
+    }
+#undef SRQ_MASK
+  }
+  hipLaunchKernelGGL(rows_mask_kernel, grid, block, 0, st, X, cols, ldx, thresh, mask, words, counts);
   return hipGetLastError();
 }
 
 hipError_t launch_scatter_mask(const uint64_t* mask, int64_t nvec, int64_t veclen, const int8_t* Q, int64_t ldq,
-                               const int32_t* ptr, int32_t* idx, int8_t* val, int64_t capacity, hipStream_t st) {
+                               const int32_t* ptr, int32_t* idx, int8_t* val, int64_t capacity, int8_t* dense,
+                               int64_t ldd, hipStream_t st) {
   if (nvec <= 0 || veclen <= 0) return hipSuccess;
-  hipLaunchKernelGGL(scatter_mask_kernel, dim3((unsigned)nvec), dim3(256), 0, st, mask, mask_words(veclen), Q,
-                     ldq, ptr, idx, val, capacity);
+  hipLaunchKernelGGL(scatter_mask_kernel, dim3((unsigned)nvec), dim3(256), 0, st, mask, mask_words(veclen),
+                     veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd);
+  return hipGetLastError();
+}
+
+hipError_t launch_scan_pair(const int32_t* t0, int64_t n0, int32_t* p0, int64_t* z0, const int32_t* t1,
+                            int64_t n1, int32_t* p1, int64_t* z1, hipStream_t st) {
+  hipLaunchKernelGGL(scan_pair_kernel, dim3(2), dim3(1024), 0, st, t0, n0, p0, z0, t1, n1, p1, z1);
   return hipGetLastError();
 }
 
