@@ -49,7 +49,7 @@ def gpu_thetas(srq, b, Ad, Bd, density):
         dv = d.view(-1, 1) if axis == 0 else d.view(1, -1)
         rho = (X.abs() / dv).reshape(-1)
         keep = int(round(rho.numel() * density))
-        return float(torch.kthvalue(rho, rho.numel() - keep).values.item())
+        return float(torch.sort(rho).values[rho.numel() - keep - 1].item())
     return cal(Ad, drow, 0), cal(Bd, dcol, 1)
 
 
