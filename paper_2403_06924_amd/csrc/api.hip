@@ -552,8 +552,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     {
     StageTimer tm(h, st, SRQ_STAGE_SELECT);
     // line 7: GetAvgVec, and the thresholds of Eq. avgQuan
-    SRQ_HIP(h, launch_reduce_means(p.row_part, gemm_tiles_n(M, N), M, N, theta_a, p.drow, p.t_a, st));
-    SRQ_HIP(h, launch_reduce_means(p.col_part, gemm_tiles_m(M, N), N, M, theta_b, p.dcol, p.t_b, st));
+    SRQ_HIP(h, launch_reduce_means_pair(p.row_part, gemm_tiles_n(M, N), M, N, theta_a, p.drow, p.t_a,
+                                        p.col_part, gemm_tiles_m(M, N), N, M, theta_b, p.dcol, p.t_b, st));
     im.drow = p.drow; im.dcol = p.dcol; im.t_a = p.t_a; im.t_b = p.t_b;
     // lines 8-10: Reduce.  Keep-bits and per-vector counts, then the prefix scans
     int64_t chk = select_chunks(K);

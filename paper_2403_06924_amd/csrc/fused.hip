@@ -274,8 +274,12 @@ __global__ __launch_bounds__(256) void rows_mask_vec_kernel(const float* __restr
                    (fabsf(x[i].z) > t ? 4u : 0u) | (fabsf(x[i].w) > t ? 8u : 0u);
     if (c4 >= n4) nib = 0;
     total += __popc(nib);
-    unsigned hi = __shfl_down(nib, 1, 64);
-    if (!(threadIdx.x & 1) && (c4 >> 1) < mask_stride) mrow[c4 >> 1] = (uint8_t)(nib | (hi << 4));
+    // eight neighbouring lanes assemble one 32-bit piece of the mask
+    unsigned b8 = nib | (__shfl_down(nib, 1, 64) << 4);
+    unsigned b16 = b8 | (__shfl_down(b8, 2, 64) << 8);
+    unsigned b32 = b16 | (__shfl_down(b16, 4, 64) << 16);
+    if (!(threadIdx.x & 7) && (c4 >> 1) < mask_stride)
+      *reinterpret_cast<unsigned*>(mrow + (c4 >> 1)) = b32;
   }
   for (int off = 32; off > 0; off >>= 1) total += __shfl_xor(total, off, 64);
   if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = total;

@@ -276,14 +276,28 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(int64_t M, int64_t N, int6
       }
     }
     if (sums) {
+      // Row sums: r[v] is this lane's share of row v of the band.  A reduce-scatter butterfly
+      // over the 32 lanes of the half-wave (halving the live values at each exchange) leaves
+      // the total of row v = cl >> 1 in lanes cl and cl ^ 1: 16 shuffles instead of 80.
+      float r[16];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        float r;
-        if (C::TN == 4) r = (ad[0][v] + ad[1][v]) + (ad[2][v] + ad[3][v]);
-        else r = ad[0][v] + ad[C::TN - 1][v];
-        for (int off = 16; off > 0; off >>= 1) r += __shfl_xor(r, off, 64);
-        if (cl == 0) red[wn * RED + rbase + 8 * (v >> 2) + (v & 3)] = (double)r;
+        if (C::TN == 4) r[v] = (ad[0][v] + ad[1][v]) + (ad[2][v] + ad[3][v]);
+        else r[v] = ad[0][v] + ad[C::TN - 1][v];
       }
+#pragma unroll
+      for (int n = 8, o = 16; n >= 1; n >>= 1, o >>= 1) {
+        const bool up = (cl & o) != 0;
+#pragma unroll
+        for (int i = 0; i < n; ++i) {
+          float send = up ? r[i] : r[i + n];
+          float keep = up ? r[i + n] : r[i];
+          r[i] = keep + __shfl_xor(send, o, 64);
+        }
+      }
+      r[0] += __shfl_xor(r[0], 1, 64);
+      const int v = cl >> 1;
+      if (!(cl & 1)) red[wn * RED + rbase + 8 * (v >> 2) + (v & 3)] = (double)r[0];
 #pragma unroll
       for (int b = 0; b < C::TN; ++b) {
         float t8[8], t4[4];

@@ -27,6 +27,25 @@ __global__ void reduce_means_kernel(const double* __restrict__ part, int64_t npa
   if (thresh) thresh[v] = theta * m;
 }
 
+// both mean vectors of one product in a single launch: vectors [0, n0) are rows, the rest columns
+__global__ void reduce_means_pair_kernel(const double* __restrict__ part0, int64_t nparts0, int64_t n0,
+                                         double count0, float theta0, float* __restrict__ mean0,
+                                         float* __restrict__ thresh0, const double* __restrict__ part1,
+                                         int64_t nparts1, int64_t n1, double count1, float theta1,
+                                         float* __restrict__ mean1, float* __restrict__ thresh1) {
+  int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= n0 + n1) return;
+  const bool second = v >= n0;
+  if (second) v -= n0;
+  const double* part = second ? part1 : part0;
+  const int64_t nparts = second ? nparts1 : nparts0, nvec = second ? n1 : n0;
+  double s = 0.0;
+  for (int64_t p = 0; p < nparts; ++p) s += part[p * nvec + v];
+  float m = (float)(s / (second ? count1 : count0));
+  (second ? mean1 : mean0)[v] = m;
+  (second ? thresh1 : thresh0)[v] = (second ? theta1 : theta0) * m;
+}
+
 // ---- vectors are rows: one wave per (row, chunk of kSelChunk consecutive elements) ----
 template <bool SCATTER>
 __global__ __launch_bounds__(256) void select_rows_kernel(
@@ -190,6 +209,17 @@ hipError_t launch_reduce_means(const double* part, int64_t nparts, int64_t nvec,
   if (nvec <= 0) return hipSuccess;
   hipLaunchKernelGGL(reduce_means_kernel, dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, part,
                      nparts, nvec, (double)count, theta, mean, thresh);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_means_pair(const double* part0, int64_t nparts0, int64_t n0, int64_t count0, float theta0,
+                                    float* mean0, float* thresh0, const double* part1, int64_t nparts1,
+                                    int64_t n1, int64_t count1, float theta1, float* mean1, float* thresh1,
+                                    hipStream_t st) {
+  if (n0 + n1 <= 0) return hipSuccess;
+  hipLaunchKernelGGL(reduce_means_pair_kernel, dim3((unsigned)((n0 + n1 + 255) / 256)), dim3(256), 0, st, part0,
+                     nparts0, n0, (double)count0, theta0, mean0, thresh0, part1, nparts1, n1, (double)count1,
+                     theta1, mean1, thresh1);
   return hipGetLastError();
 }
 

@@ -112,6 +112,11 @@ hipError_t launch_scan_pair(const int32_t* t0, int64_t n0, int32_t* p0, int64_t*
 hipError_t launch_reduce_means(const double* part, int64_t nparts, int64_t nvec, int64_t count,
                                float theta, float* mean, float* thresh, hipStream_t st);
 
+hipError_t launch_reduce_means_pair(const double* part0, int64_t nparts0, int64_t n0, int64_t count0, float theta0,
+                                    float* mean0, float* thresh0, const double* part1, int64_t nparts1,
+                                    int64_t n1, int64_t count1, float theta1, float* mean1, float* thresh1,
+                                    hipStream_t st);
+
 // INT8 GEMM, both operands K-contiguous
 int gemm_tile_m();                          // smallest tile extents (upper bound on tile counts)
 int gemm_tile_n();
