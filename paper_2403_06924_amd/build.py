@@ -11,13 +11,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsrq.so")
-SOURCES = ["api.hip", "quantize.hip", "fused.hip", "select.hip", "gemm.hip", "spmm.hip"]
+SOURCES = ["api.hip", "quantize.hip", "fused.hip", "select.hip", "gemm.hip", "gemm_persistent.hip", "spmm.hip"]
 
 # -ffp-contract=off: the dequantize / residual steps are defined with one rounding per
 # operation, so no multiply-add may be fused.  Packed FP32 instructions stay off.
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wno-inline-asm",
     "-Wno-unused-command-line-argument", "-Wno-unknown-attributes",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

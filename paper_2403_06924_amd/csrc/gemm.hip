@@ -12,6 +12,7 @@
 // global -> registers -> LDS, double buffered so that the loads of step t+1 are in flight
 // while step t is multiplied.  LDS rows are padded by 16 bytes so the 16-byte fragment reads
 // of 16 consecutive rows fall on distinct banks.
+
 #include "srq_internal.h"
 
 namespace srq {
@@ -204,11 +205,13 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(int64_t M, int64_t N, int6
           if (i < NPIECE) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
       } else {
+        // fragment reads up front, one per MFMA, so the last one is back long before step s+1
 #pragma unroll
         for (int i = 0; i < NFRAG; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / NFRAG, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
           __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA > NFRAG ? NMFMA - NFRAG : 1, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -378,6 +381,8 @@ int64_t gemm_tiles_n(int64_t M, int64_t N) { int t = use_big_tiles(M, N) ? 256 :
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
                           const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st) {
   if (M <= 0 || N <= 0) return hipSuccess;
+  if (gemm_persistent_ok(M, N, K, Qa, lda, Qb, ldb, ep))
+    return launch_gemm_i8_persistent(M, N, K, Qa, lda, Qb, ldb, ep, st);
   // fast path: every 16-byte piece is aligned and inside [0,K)
   bool fast = ((reinterpret_cast<uintptr_t>(Qa) | reinterpret_cast<uintptr_t>(Qb)) & 15) == 0 &&
               (lda % 16) == 0 && (ldb % 16) == 0 && K > 0 && (K % 64) == 0;

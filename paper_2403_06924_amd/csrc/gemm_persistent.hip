@@ -1,0 +1,347 @@
+// Persistent variant of the INT8 GEMM for full, aligned problems (M, N multiples of 256, K a
+// multiple of 128, 16-byte aligned operands): the shape of every large workload.
+//
+// Same output tile as gemm_i8_kernel (256 x 256 per 4-wave workgroup, 128 x 128 per wave,
+// v_mfma_i32_32x32x32_i8) with two differences made for gfx950:
+//
+//  * operand tiles go from global memory straight into LDS (global_load_lds_dwordx4): no
+//    staging registers and no ds_write instructions.  The hardware writes the 64 lanes of one
+//    load to 1 KiB of consecutive LDS bytes, so the tile rows are unpadded (128 B) and bank
+//    conflicts of the 16-byte fragment reads are avoided by an XOR swizzle instead: the 16-byte
+//    piece s of row r sits at position s ^ ((r >> 1) & 7), applied on the global-address side
+//    when loading and on the LDS-address side when reading;
+//  * a workgroup walks over several output tiles and the stream of staged K-tiles never drains
+//    between them: while one tile's epilogue runs, the first K-tiles of the next are already
+//    landing in LDS (they need no registers), and the epilogue's stores retire while the next
+//    tile is multiplied.  A one-tile-per-workgroup launch pays launch, prologue latency and
+//    drain once per tile - four times per CU at 8192^3, since only one workgroup fits a CU.
+#include "srq_internal.h"
+
+namespace srq {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 256, BN = 256, BK = 128, KS = BK / 32;
+constexpr int kOperand = BM * BK;                   // 32 KiB per operand tile
+constexpr int kStage = 2 * kOperand;                // A tile then B tile
+constexpr int TM = 4, TN = 4;                       // 32x32 MFMA tiles per wave
+constexpr int kLdsScales = 2 * kStage;              // float[BM + BN]
+constexpr int kLdsRed = kLdsScales + (BM + BN) * 4; // double[2][256]
+constexpr int kLdsBytes = kLdsRed + 2 * 256 * 8;
+
+// tile coordinates of the vb-th tile in launch order: XCD-contiguous bands, groups of 8 rows
+__device__ __forceinline__ void tile_of(int64_t vb, int64_t tiles_m, int64_t tiles_n, int64_t& tm, int64_t& tn) {
+  const int64_t total = tiles_m * tiles_n, per = total / 8;
+  int64_t bid = vb;
+  if (per > 0 && bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
+  const int64_t g = 8;
+  int64_t grp = bid / (g * tiles_n), first = grp * g;
+  int64_t rows_in = tiles_m - first < g ? tiles_m - first : g;
+  int64_t in = bid - grp * g * tiles_n;
+  tm = first + in % rows_in;
+  tn = in / rows_in;
+}
+
+// One wave-wide 16-byte-per-lane load from global memory into LDS: lane l's bytes land at
+// lds_base + 16*l.  Issued as inline assembly so that its completion is waited for explicitly
+// (wait_loads) right before the barrier that publishes the tile, not before every LDS read.
+__device__ __forceinline__ void load_to_lds(const int8_t* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
+}
+__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+
+template <int MODE, bool SUMS, bool SCALE>
+__global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int64_t N, int64_t K,
+                                                                 const int8_t* __restrict__ Qa, int64_t lda,
+                                                                 const int8_t* __restrict__ Qb, int64_t ldb,
+                                                                 int64_t tiles_m, int64_t tiles_n,
+                                                                 GemmEpilogue ep) {
+  extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
+  float* sc_row = reinterpret_cast<float*>(lds + kLdsScales);
+  float* sc_col = sc_row + BM;
+  double* red = reinterpret_cast<double*>(lds + kLdsRed);
+  // LDS byte address of the first stage (an address-space-3 pointer is a 32-bit offset)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) int8_t*)lds);
+
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));                     // keeps per-thread offsets from being hoisted out of the tile loop
+  const int lane = tid & 63, w = tid >> 6, wm = w >> 1, wn = w & 1;
+  const int64_t total = tiles_m * tiles_n, G = gridDim.x, nk = K / BK;
+
+  // ---- loader: wave w fetches rows 64w .. 64w+63 of each operand tile, eight rows per load.
+  // Lane l of load j covers row 64w + 8j + l/8 and LDS piece l%8, which holds the logical piece
+  // (l%8) ^ ((row >> 1) & 7); (row >> 1) & 7 = ((l >> 4) + 4j) & 7 depends on j only through
+  // its parity.
+  const int lrow = lane >> 3;
+  const int64_t goff_a0 = (int64_t)lrow * lda + 16 * ((lane & 7) ^ ((lane >> 4) & 7));
+  const int64_t goff_a1 = (int64_t)lrow * lda + 16 * ((lane & 7) ^ (((lane >> 4) + 4) & 7));
+  const int64_t goff_b0 = (int64_t)lrow * ldb + 16 * ((lane & 7) ^ ((lane >> 4) & 7));
+  const int64_t goff_b1 = (int64_t)lrow * ldb + 16 * ((lane & 7) ^ (((lane >> 4) + 4) & 7));
+  int64_t vba = blockIdx.x, kta = 0;                // cursor of the K-tile being fetched
+  const int8_t *pa, *pb;                            // row 64w of that K-tile in A and in B
+  auto point = [&]() {
+    int64_t tm, tn;
+    tile_of(vba, tiles_m, tiles_n, tm, tn);
+    pa = Qa + (tm * BM + 64 * w) * lda + kta * BK;
+    pb = Qb + (tn * BN + 64 * w) * ldb + kta * BK;
+  };
+  auto advance = [&]() {
+    if (kta + 1 < nk) {
+      ++kta;
+      pa += BK;
+      pb += BK;
+    } else if (vba + G < total) {
+      vba += G;
+      kta = 0;
+      point();
+    }                                               // else stay on the last K-tile (harmless re-fetch)
+  };
+  // load i (0..15) of the K-tile at the cursor into LDS buffer `stage`: even i -> A, odd i -> B
+  auto issue_load = [&](int stage, int i) {
+    // wave-uniform by construction; readfirstlane tells the compiler so (it feeds M0)
+    const uint32_t la = __builtin_amdgcn_readfirstlane(lds0 + stage * kStage + (64 * w) * BK);
+    const int j = i >> 1;
+    if (i & 1)
+      load_to_lds(pb + (int64_t)(8 * j) * ldb + ((j & 1) ? goff_b1 : goff_b0), la + kOperand + j * 8 * BK);
+    else
+      load_to_lds(pa + (int64_t)(8 * j) * lda + ((j & 1) ? goff_a1 : goff_a0), la + j * 8 * BK);
+  };
+  auto issue_loads = [&](int stage) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) issue_load(stage, i);
+  };
+
+  // ---- fragment reads: lane (frow, kh) reads logical piece 2*step + kh of its rows
+  const int frow = lane & 31, kh = lane >> 5, key = (frow >> 1) & 7;
+  const int a_row = (wm * (BM / 2) + frow) * BK;
+  const int b_row = kOperand + (wn * (BN / 2) + frow) * BK;
+  int xoff[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) xoff[s] = 16 * ((2 * s + kh) ^ key);
+  v4i fa[2][TM], fb[2][TN];
+  auto fread = [&](int stage, int step, int slot) {
+    const int8_t* As = lds + stage * kStage + a_row + xoff[step];
+    const int8_t* Bs = lds + stage * kStage + b_row + xoff[step];
+#pragma unroll
+    for (int t = 0; t < TM; ++t) fa[slot][t] = *reinterpret_cast<const v4i*>(As + t * 32 * BK);
+#pragma unroll
+    for (int t = 0; t < TN; ++t) fb[slot][t] = *reinterpret_cast<const v4i*>(Bs + t * 32 * BK);
+  };
+
+  // ---- the output tile being multiplied
+  int64_t vb = blockIdx.x, tile_m, tile_n;
+  tile_of(vb, tiles_m, tiles_n, tile_m, tile_n);
+  float sreg_row = ep.s_row[tile_m * BM + tid], sreg_col = ep.s_col[tile_n * BN + tid];
+
+  point();
+  issue_loads(0);
+  advance();
+  wait_loads();
+  __syncthreads();
+  issue_loads(1);
+  advance();
+  fread(0, 0, 0);
+
+  v16i acc[TM][TN];
+#pragma unroll
+  for (int a = 0; a < TM; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
+
+  const int64_t my_tiles = (total - blockIdx.x + G - 1) / G;
+  int g = 0;                                        // parity of the K-tile stream across tiles
+  for (int64_t tile = 0; tile < my_tiles; ++tile) {
+  for (int64_t kt = 0; kt < nk; ++kt, ++g) {
+    const int cur = g & 1;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      if (s == KS - 1) {
+        // K-tile g+1 (loads issued one whole K-tile ago) must have landed; after the barrier
+        // everybody is also done reading buffer `cur`, which takes K-tile g+2.  The 16 loads
+        // are issued one after each MFMA of this step, in program order.
+        wait_loads();
+        __syncthreads();
+        fread(cur ^ 1, 0, (s + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) {
+            acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
+            issue_load(cur, a * TN + b);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+      } else {
+        fread(cur, s + 1, (s + 1) & 1);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
+        // issue order: one fragment read after each of the first eight MFMAs (0x008 MFMA, 0x100 DS read)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    advance();
+  }
+
+    // ================= epilogue of tile (tile_m, tile_n); no bounds checks: tiles are full
+    sc_row[tid] = sreg_row;
+    sc_col[tid] = sreg_col;
+    __syncthreads();
+    const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
+    const int half = lane >> 5, cl = lane & 31;
+    const int cbase = wn * (BN / 2) + cl;
+    double colsum[TN];
+    float scol[TN];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+      colsum[b] = 0.0;
+      scol[b] = sc_col[cbase + b * 32];
+    }
+#pragma unroll
+    for (int a = 0; a < TM; ++a) {
+      const int rbase = wm * (BM / 2) + a * 32 + 4 * half;
+      float* cband = ep.C + (m0 + rbase) * ep.ldc + n0 + cbase;
+      float x[TN][16];
+      if (MODE == kGemmAccum) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) x[b][v] = cband[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32];
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int ro = 8 * (v >> 2) + (v & 3);
+        const float srow = sc_row[rbase + ro];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+          const float d = (float)acc[a][b][v] * (srow * scol[b]);
+          float out = MODE == kGemmFirst ? d : x[b][v] + d;
+          if (SCALE) {
+            out = ep.alpha * out;
+            if (ep.beta != 0.f) out = out + ep.beta * ep.Cin[(m0 + rbase + ro) * ep.ldcin + n0 + cbase + b * 32];
+          }
+          cband[(int64_t)ro * ep.ldc + b * 32] = out;
+          if (SUMS) x[b][v] = fabsf(d);
+          acc[a][b][v] = 0;
+        }
+      }
+      if (SUMS) {
+        // row sums by a reduce-scatter butterfly over the 32 lanes that share a row
+        float r[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) r[v] = (x[0][v] + x[1][v]) + (x[2][v] + x[3][v]);
+#pragma unroll
+        for (int n = 8, o = 16; n >= 1; n >>= 1, o >>= 1) {
+          const bool up = (cl & o) != 0;
+#pragma unroll
+          for (int i = 0; i < n; ++i) {
+            float send = up ? r[i] : r[i + n];
+            float keep = up ? r[i + n] : r[i];
+            r[i] = keep + __shfl_xor(send, o, 64);
+          }
+        }
+        r[0] += __shfl_xor(r[0], 1, 64);
+        const int v = cl >> 1;
+        if (!(cl & 1)) red[wn * 256 + rbase + 8 * (v >> 2) + (v & 3)] = (double)r[0];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+          float t8[8], t4[4];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) t8[i] = x[b][2 * i] + x[b][2 * i + 1];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) t4[i] = t8[2 * i] + t8[2 * i + 1];
+          colsum[b] += (double)((t4[0] + t4[1]) + (t4[2] + t4[3]));
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (SUMS) {
+      __syncthreads();
+      ep.row_part[tile_n * M + m0 + tid] = red[tid] + red[256 + tid];
+      __syncthreads();
+#pragma unroll
+      for (int b = 0; b < TN; ++b) {
+        double c = colsum[b];
+        c += __shfl_xor(c, 32, 64);
+        if (half == 0) red[wm * 256 + cbase + b * 32] = c;
+      }
+      __syncthreads();
+      ep.col_part[tile_m * N + n0 + tid] = red[tid] + red[256 + tid];
+    }
+    // next output tile of this workgroup
+    vb += G;
+    if (vb < total) {
+      tile_of(vb, tiles_m, tiles_n, tile_m, tile_n);
+      sreg_row = ep.s_row[tile_m * BM + tid];
+      sreg_col = ep.s_col[tile_n * BN + tid];
+    }
+  }
+  wait_loads();                                     // nothing may still be writing LDS when the wave ends
+}
+
+}  // namespace
+
+bool gemm_persistent_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb,
+                        int64_t ldb, const GemmEpilogue& ep) {
+  if (ep.D_int || ep.D_F_copy) return false;                 // parity-check outputs use the plain kernel
+  if (M <= 0 || N <= 0 || K <= 0 || (M % BM) || (N % BN) || (K % BK)) return false;
+  if (((reinterpret_cast<uintptr_t>(Qa) | reinterpret_cast<uintptr_t>(Qb)) & 15) || (lda % 16) || (ldb % 16))
+    return false;
+  return (M / BM) * (N / BN) >= 512;
+}
+
+hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
+                                     const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st) {
+  static int num_cu = 0;
+  if (!num_cu) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return e;
+    num_cu = prop.multiProcessorCount;
+  }
+  const int64_t tm = M / BM, tn = N / BN;
+  int64_t wgs = num_cu / 8 * 8;                              // one workgroup per CU, a multiple of the 8 XCDs
+  if (wgs < 8) wgs = 8;
+  if (wgs > tm * tn) wgs = tm * tn;
+  const bool sums = ep.mode == kGemmFirst && ep.row_part != nullptr;
+  const bool scale = ep.final_scale != 0;
+  void (*kern)(int64_t, int64_t, int64_t, const int8_t*, int64_t, const int8_t*, int64_t, int64_t, int64_t,
+               GemmEpilogue);
+  if (ep.mode == kGemmFirst) {
+    kern = sums ? (scale ? gemm_i8_persistent_kernel<kGemmFirst, true, true>
+                         : gemm_i8_persistent_kernel<kGemmFirst, true, false>)
+                : (scale ? gemm_i8_persistent_kernel<kGemmFirst, false, true>
+                         : gemm_i8_persistent_kernel<kGemmFirst, false, false>);
+  } else {
+    kern = scale ? gemm_i8_persistent_kernel<kGemmAccum, false, true>
+                 : gemm_i8_persistent_kernel<kGemmAccum, false, false>;
+  }
+  static const void* attr_done[8] = {nullptr};
+  bool done = false;
+  for (const void* p : attr_done) done |= p == reinterpret_cast<const void*>(kern);
+  if (!done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    for (auto& p : attr_done)
+      if (!p) { p = reinterpret_cast<const void*>(kern); break; }
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), kLdsBytes, st, M, N, K, Qa, lda, Qb, ldb, tm, tn, ep);
+  return hipGetLastError();
+}
+
+}  // namespace srq

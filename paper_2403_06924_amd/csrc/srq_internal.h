@@ -124,6 +124,11 @@ int64_t gemm_tiles_m(int64_t M, int64_t N);  // tile counts of the configuration
 int64_t gemm_tiles_n(int64_t M, int64_t N);
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
                           const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st);
+// persistent-workgroup variant for full, aligned, large problems (chosen inside launch_gemm_i8)
+bool gemm_persistent_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb,
+                        int64_t ldb, const GemmEpilogue& ep);
+hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
+                                     const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st);
 
 // CSR (vector-major) -> zero-filled dense vector-major codes
 hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* val, int64_t nvec,
