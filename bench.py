@@ -41,6 +41,21 @@ def parse():
     return ap.parse_args()
 
 
+def recorded_traffic(workload):
+    """HBM bytes per GEMM launch from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy); None when no summary exists."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        "bench_%s_hbm_traffic.md" % workload)
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("TRAFFIC_BYTES_PER_GEMM_LAUNCH"):
+                    return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def calibrate_theta(torch, X, dvec, axis, density):
     """Harness only: theta such that about `density` of the entries have |x| > theta*dvec."""
     d = dvec.view(-1, 1) if axis == 0 else dvec.view(1, -1)
@@ -161,8 +176,8 @@ def main():
     if sum(gemm_ms) >= sum(t for t, _ in valu_ms):
         avg = sum(gemm_ms) / len(gemm_ms)
         ach = ops / (avg * 1e-3) / 1e12
-        roof = {"kernel": "gemm_i8_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_INT8_TOPS,
-                "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS, "traffic": None,
+        roof = {"kernel": "gemm_i8_persistent_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_INT8_TOPS,
+                "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS, "traffic": recorded_traffic(args.workload),
                 "launches_per_step": len(gemm_ms), "avg_launch_ms": avg}
     else:
         t = sum(t for t, _ in valu_ms)
