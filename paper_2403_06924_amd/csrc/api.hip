@@ -14,9 +14,14 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-// density at and above which the matrix-core execution of the sparse products is chosen
-// by SRQ_STRATEGY_AUTO (measured crossover of the two kernels on MI355X)
-constexpr double kAutoMfmaDensity = 0.02;
+// Densities at and above which SRQ_STRATEGY_AUTO runs a sparse product on the matrix cores
+// (the paper's switch between SPMM and GEMM, Algorithm 1 lines 11-15, with the ratio of the
+// two kernels' throughputs on MI355X in place of the paper's eta).  Measured at 8192^3: the
+// vector-ALU kernel takes 0.19 ms + 0.30 ms per percent of density for A' (rows of C written
+// straight), 0.25 ms + 0.36 ms per percent for B' (columns of C, through LDS); the expanded
+// operand on the matrix cores takes 0.52-0.58 ms at any density.
+constexpr double kAutoMfmaDensityA = 0.012;
+constexpr double kAutoMfmaDensityB = 0.0075;
 
 struct Carver {
   char* base;
@@ -420,7 +425,7 @@ srq_status_t srq_spmm_accumulate(srq_handle_t h, srq_axis_t side, srq_strategy_t
   ep.alpha = 1.f;
   const int64_t cap = 2147483647LL;
   if (strategy == SRQ_STRATEGY_CSR_VALU) {
-    SRQ_HIP(h, launch_spmm_valu(side == SRQ_AXIS_ROW ? 0 : 1, nvec, nelem, ptr, idx, val, cap, Rq, ldr, ep, st));
+    SRQ_HIP(h, launch_spmm_valu(side == SRQ_AXIS_ROW ? 0 : 1, nvec, nelem, K, ptr, idx, val, cap, Rq, ldr, ep, st));
   } else {
     int8_t* dense = reinterpret_cast<int8_t*>(h->ws);
     int64_t ldd = (K + 15) / 16 * 16;
@@ -581,13 +586,13 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
         return SRQ_STATUS_CAPACITY;
       }
       double da = (double)na / ((double)M * (double)K), db = (double)nb / ((double)N * (double)K);
-      auto pick = [&](double d) {
+      auto pick = [&](double d, double crossover) {
         if (d >= (double)dense_fallback_density) return 3;
-        if (strategy == SRQ_STRATEGY_AUTO) return d >= kAutoMfmaDensity ? 2 : 1;
+        if (strategy == SRQ_STRATEGY_AUTO) return d >= crossover ? 2 : 1;
         return (int)strategy;
       };
-      if (term_a) path_a = pick(da);
-      if (term_b) path_b = pick(db);
+      if (term_a) path_a = pick(da, kAutoMfmaDensityA);
+      if (term_b) path_b = pick(db, kAutoMfmaDensityB);
     } else {
       if (term_a) path_a = (int)strategy;
       if (term_b) path_b = (int)strategy;
@@ -645,7 +650,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     e1.final_scale = scale_needed && path_b == 0;
     if (path_a == 1) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
-      SRQ_HIP(h, launch_spmm_valu(0, M, N, p.a_ptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, e1, st));
+      SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.a_ptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, e1, st));
     } else if (path_a == 2) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_gemm_i8(M, N, K, p.Ad, K, p.RB_int, K, e1, st));
@@ -659,7 +664,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     e2.final_scale = scale_needed;
     if (path_b == 1) {
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
-      SRQ_HIP(h, launch_spmm_valu(1, N, M, p.b_ptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, e2, st));
+      SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.b_ptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, e2, st));
     } else if (path_b == 2) {
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
       SRQ_HIP(h, launch_gemm_i8(M, N, K, p.RA_int, K, p.Bd, K, e2, st));

@@ -135,7 +135,7 @@ hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* 
                           int64_t veclen, int64_t capacity, int8_t* dense, int64_t ld, hipStream_t st);
 
 // VALU SpMM.  out[v, e] = sum_p val[p] * R[idx[p]*ldr + e];  side 0: C[v, e], side 1: C[e, v]
-hipError_t launch_spmm_valu(int side, int64_t nvec, int64_t nelem, const int32_t* ptr,
+hipError_t launch_spmm_valu(int side, int64_t nvec, int64_t nelem, int64_t K, const int32_t* ptr,
                             const int32_t* idx, const int8_t* val, int64_t capacity, const int8_t* R,
                             int64_t ldr, const GemmEpilogue& ep, hipStream_t st);
 

@@ -197,6 +197,39 @@ def test_spmm_accumulate_bit_exact(srq, b, shape, side, strategy):
     assert (host(Cd) == ref_C).all()
 
 
+@pytest.mark.parametrize("shape", [(100, 520, 300), (264, 1032, 96), (2048, 1544, 640)])
+@pytest.mark.parametrize("side", [0, 1])
+@pytest.mark.parametrize("density", [0.3, 0.02])
+@pytest.mark.parametrize("want_int", [False, True])
+def test_spmm_tiled_kernel_bit_exact(srq, b, shape, side, density, want_int):
+    """Aligned operands take the tiled vector-ALU kernel: several 64-pair batches per vector,
+    pair counts that are not multiples of the unroll, empty vectors, a ragged block of vectors
+    and a ragged last chunk of elements; with and without the INT32 side output (the two
+    epilogue variants of side 0)."""
+    M, N, K = shape
+    rng = np.random.default_rng(M + 3 * N + 5 * K + side)
+    nvec, nelem = (M, N) if side == 0 else (N, M)
+    Qs = rng.integers(-127, 128, size=(nvec, K)).astype(np.int8)
+    mask = rng.random((nvec, K)) < density
+    mask[0] = False
+    mask[nvec // 2] = False
+    mask[nvec - 1] = True                                                  # a full vector
+    c = o.compress(mask, Qs, "row")
+    Rk = rng.integers(-127, 128, size=(K, nelem)).astype(np.int8)
+    s_row = rng.random(M).astype(F32) + F32(0.1)
+    s_col = rng.random(N).astype(F32) + F32(0.1)
+    C0 = rng.standard_normal((M, N)).astype(F32)
+    Cd = dev(C0)
+    DR = srq.spmm_accumulate(side, 1, M, N, K, dev(c.ptr), dev(c.idx), dev(c.val), dev(Rk), dev(s_row),
+                             dev(s_col), Cd, want_int=want_int)
+    sparse = np.where(mask, Qs, 0)
+    ref_int = o.int_matmul(sparse, Rk) if side == 0 else o.int_matmul(Rk.T, sparse.T)
+    if want_int:
+        assert (host(DR) == ref_int).all()
+    ref_C = C0 + o.dequant_product(ref_int, s_row, s_col)
+    assert (host(Cd) == ref_C).all()
+
+
 # ------------------------------------------------------------------ whole path
 def check_against_oracle(srq, b, A, B, theta_a, theta_b, *, bits=8, rnd=0, strategy=1, s=2.0,
                          alpha=1.0, beta=0.0, C_in=None):
