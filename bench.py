@@ -201,6 +201,24 @@ def main():
                     "rel_err_vs_fp64_dense_residual": e_dense}
         del C64
 
+    # the paper's reference columns on the same inputs: plain vector-wise INT8 (theta = inf,
+    # "origin") and compensation with the unreduced operands (theta = 0, "full"); and the part
+    # of a step that remains when both operands arrive quantized (everything but a1 and a5)
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / reps * 1e3
+    inf = float("inf")
+    ms_plain = timed(lambda: h.compensated_gemm(Ad, Bd, inf, inf, out=Cd))
+    ms_full = timed(lambda: h.compensated_gemm(Ad, Bd, 0.0, 0.0, dense_fallback_density=0.0, out=Cd))
+    variants = {"plain_int8_ms": ms_plain, "plain_int8_tops": ops / (ms_plain * 1e-3) / 1e12,
+                "dense_compensated_ms": ms_full, "dense_compensated_tops": ops / (ms_full * 1e-3) / 1e12,
+                "prequantized_ms": sum(v for k, v in stage_ms.items() if k not in ("quantize", "residual"))}
+
     out = {
         "metric": "effective TOPS (2MNK/s) of compensated INT8 GEMM", "value": value, "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -214,6 +232,7 @@ def main():
         "density_a": st["nnz_a"] / (M * K), "density_b": st["nnz_b"] / (N * K),
         "path_a": st["path_a"], "path_b": st["path_b"],
         "stage_ms": stage_ms,
+        "variants": variants,
         "roofline": roof,
         "accuracy": accuracy,
     }

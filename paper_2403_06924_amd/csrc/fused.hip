@@ -287,9 +287,14 @@ __global__ __launch_bounds__(256) void rows_mask_vec_kernel(const float* __restr
   if (threadIdx.x == 0) counts[row] = sm[0] + sm[1] + sm[2] + sm[3];
 }
 
-// ---- compaction: one block per vector; a thread owns whole mask words and walks their set bits.
-// Optionally also writes the vector expanded to zero-filled dense codes (operand of the
-// matrix-core execution of the sparse product).
+// ---- compaction: one block per vector, a quarter of the vector per wave.  A wave first counts
+// the kept entries of its quarter from the mask words (that fixes where it writes), then walks
+// the quarter 256 elements at a time, four per lane: the position of a lane's first kept entry
+// is the wave's running offset plus the number of kept entries in lower lanes, obtained from
+// three ballots of the bits of the lane's own count (0..4).  Neighbouring lanes therefore write
+// neighbouring slots of idx / val at any density.  Optionally the vector is also written
+// expanded to zero-filled dense codes (operand of the matrix-core execution of the sparse
+// product), from the same registers.
 __global__ __launch_bounds__(256) void scatter_mask_kernel(const uint64_t* __restrict__ mask, int64_t words,
                                                            int64_t veclen, const int8_t* __restrict__ Q,
                                                            int64_t ldq, const int32_t* __restrict__ ptr,
@@ -300,56 +305,65 @@ __global__ __launch_bounds__(256) void scatter_mask_kernel(const uint64_t* __res
   const int64_t v = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const uint64_t* mv = mask + v * words;
+  const uint32_t* mv32 = reinterpret_cast<const uint32_t*>(mv);
   const int8_t* qv = Q + v * ldq;
-  if (dense) {
-    // dense[e] = kept ? code : 0, eight codes (one mask byte) per step
-    int8_t* dv = dense + v * ldd;
-    const uint8_t* mb = reinterpret_cast<const uint8_t*>(mv);
-    const bool vec = ((reinterpret_cast<uintptr_t>(qv) | reinterpret_cast<uintptr_t>(dv)) & 7) == 0;
-    const int64_t n8 = veclen >> 3;
-    for (int64_t i = tid; i < n8; i += 256) {
-      unsigned bits = mb[i];
-      if (vec) {
-        uint2 c = *reinterpret_cast<const uint2*>(qv + i * 8);
-        unsigned lo = 0, hi = 0;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          lo |= (bits >> b & 1u) ? (0xffu << (8 * b)) : 0u;
-          hi |= (bits >> (b + 4) & 1u) ? (0xffu << (8 * b)) : 0u;
-        }
-        *reinterpret_cast<uint2*>(dv + i * 8) = make_uint2(c.x & lo, c.y & hi);
+  int8_t* dv = dense ? dense + v * ldd : nullptr;
+  const bool qvec = (reinterpret_cast<uintptr_t>(qv) & 3) == 0;
+  const bool dvec = dv && (reinterpret_cast<uintptr_t>(dv) & 3) == 0;
+  // chunks of 256 elements (four mask words); wave w owns chunks [c0, c1)
+  const int64_t nchunks = (veclen + 255) >> 8;
+  const int64_t cpw = (nchunks + 3) >> 2;
+  const int64_t c0 = w * cpw < nchunks ? w * cpw : nchunks;
+  const int64_t c1 = c0 + cpw < nchunks ? c0 + cpw : nchunks;
+  int mine = 0;
+  for (int64_t i = c0 * 4 + lane; i < c1 * 4 && i < words; i += 64) {
+    uint64_t m = mv[i];
+    const int64_t left = veclen - i * 64;                 // bits at and past veclen do not count
+    if (left < 64) m &= (1ull << left) - 1ull;
+    mine += __popcll(m);
+  }
+  for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off, 64);
+  if (lane == 0) wsum[w] = mine;
+  __syncthreads();
+  int64_t pos = ptr[v];
+  for (int i = 0; i < w; ++i) pos += wsum[i];
+  const uint64_t lower = (1ull << lane) - 1ull;
+  for (int64_t c = c0; c < c1; ++c) {
+    const int64_t e = c * 256 + 4 * lane;
+    unsigned nib = 0, code = 0;
+    if (e < veclen) {
+      nib = (mv32[e >> 5] >> (e & 31)) & 0xfu;
+      const int64_t left = veclen - e;
+      if (left < 4) nib &= (1u << left) - 1u;
+      if (qvec && left >= 4) {
+        code = *reinterpret_cast<const unsigned*>(qv + e);
       } else {
-        for (int b = 0; b < 8; ++b) dv[i * 8 + b] = (bits >> b & 1u) ? qv[i * 8 + b] : (int8_t)0;
+        for (int j = 0; j < 4 && j < left; ++j) code |= (unsigned)(uint8_t)qv[e + j] << (8 * j);
+      }
+      if (dv) {
+        const unsigned keep = ((nib & 1u) ? 0xffu : 0u) | ((nib & 2u) ? 0xff00u : 0u) |
+                              ((nib & 4u) ? 0xff0000u : 0u) | ((nib & 8u) ? 0xff000000u : 0u);
+        const unsigned out = code & keep;
+        if (dvec && left >= 4) {
+          *reinterpret_cast<unsigned*>(dv + e) = out;
+        } else {
+          for (int j = 0; j < 4 && j < left; ++j) dv[e + j] = (int8_t)(out >> (8 * j));
+        }
       }
     }
-    for (int64_t e = n8 * 8 + tid; e < veclen; e += 256)
-      dv[e] = (mb[e >> 3] >> (e & 7) & 1u) ? qv[e] : (int8_t)0;
-  }
-  // words [t*per, (t+1)*per) belong to thread t; exclusive prefix of their popcounts
-  const int64_t per = (words + 255) / 256;
-  const int64_t w0 = (int64_t)tid * per, w1 = w0 + per < words ? w0 + per : words;
-  int mine = 0;
-  for (int64_t i = w0; i < w1; ++i) mine += __popcll(mv[i]);
-  int inc = mine;
-  for (int d = 1; d < 64; d <<= 1) {
-    int y = __shfl_up(inc, d, 64);
-    if (lane >= d) inc += y;
-  }
-  if (lane == 63) wsum[w] = inc;
-  __syncthreads();
-  int64_t pos = (int64_t)ptr[v] + (inc - mine);
-  for (int i = 0; i < w; ++i) pos += wsum[i];
-  for (int64_t i = w0; i < w1; ++i) {
-    unsigned long long m = mv[i];
-    while (m) {
-      int bit = __ffsll((long long)m) - 1;
-      m &= m - 1;
-      int64_t e = i * 64 + bit;
-      if (pos < capacity) {
-        idx[pos] = (int32_t)e;
-        val[pos] = qv[e];
+    const int cnt = __popc(nib);
+    const uint64_t b0 = __ballot(cnt & 1), b1 = __ballot(cnt & 2), b2 = __ballot(cnt & 4);
+    int64_t p = pos + __popcll(b0 & lower) + 2 * __popcll(b1 & lower) + 4 * __popcll(b2 & lower);
+    pos += __popcll(b0) + 2 * __popcll(b1) + 4 * __popcll(b2);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (nib >> j & 1u) {
+        if (p < capacity) {
+          idx[p] = (int32_t)(e + j);
+          val[p] = (int8_t)(code >> (8 * j));
+        }
+        ++p;
       }
-      ++pos;
     }
   }
 }

@@ -371,3 +371,26 @@ def test_run_twice_is_deterministic(srq, b):
         outs.append((host(C).copy(), host(im["a_idx"]).copy(), host(im["t_b"]).copy()))
     for x, y in zip(*outs):
         assert x.tobytes() == y.tobytes()
+
+
+# ------------------------------------------------------------------ the paper's precision-test inputs
+@pytest.mark.parametrize("kind", ["uniform", "normal", "exponential", "poisson", "chisquare"])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_paper_distributions_1024(srq, b, kind, bits):
+    """The five non-negative distributions of the precision test (Sec. 4.1.1) at 1024^2, INT8
+    and INT4 codes: every stage against the oracle at a density of about 20 %, and the
+    direct and unreduced variants' outputs."""
+    n = 1024
+    A = wl.paper_distribution(kind, (n, n), 21)
+    B = wl.paper_distribution(kind, (n, n), 22)
+    plain = o.quantized_product(A, B, bits=bits)
+    drow, dcol = o.abs_means(plain.D_F)
+    ta = wl.theta_for_density(A, drow, "row", 0.2)
+    tb = wl.theta_for_density(B, dcol, "col", 0.2)
+    check_against_oracle(srq, b, A, B, ta, tb, bits=bits, strategy=0)
+    inf = float("inf")
+    C, _, _ = srq.compensated_gemm(dev(A), dev(B), inf, inf, bits=bits)
+    assert (host(C) == plain.D_F).all()
+    C0, _, _ = srq.compensated_gemm(dev(A), dev(B), 0.0, 0.0, bits=bits, dense_fallback_density=0.0)
+    ref0 = o.compensated_gemm(A, B, 0.0, bits=bits)
+    assert o.error_rel(ref0.C, host(C0)) <= 1e-5
