@@ -213,8 +213,9 @@ srq_status_t srq_spmm_accumulate(srq_handle_t handle, srq_axis_t side, srq_strat
  *   Cin                read only if beta != 0 (ldcin >= N); must not overlap C.
  *   stats_dev          device srq_stats_t, may be NULL.
  *   dbg                host pointer to a struct of device buffers, may be NULL.
- * Returns SRQ_STATUS_CAPACITY (after the selection ran, C not written) when a synchronising
- * mode finds more kept entries than the workspace was sized for; in non-synchronising
+ * Returns SRQ_STATUS_CAPACITY (after the first product and the selection ran: C then holds the
+ * uncorrected D_F, no correction term was added) when a synchronising mode finds more kept
+ * entries than the workspace was sized for; in non-synchronising
  * modes the compressed arrays are truncated instead and stats_dev tells. */
 srq_status_t srq_compensated_gemm(srq_handle_t handle, int64_t M, int64_t N, int64_t K, const float* A,
                                   int64_t lda, const float* B, int64_t ldb, float theta_a, float theta_b,
