@@ -66,6 +66,12 @@ typedef enum srq_strategy_t {
   SRQ_STRATEGY_CSR_MFMA = 2     /* CSR expanded to zero-filled INT8 tiles, matrix cores      */
 } srq_strategy_t;
 
+/* Granularity of the first-level scales in srq_compensated_gemm.  VECTOR is the method of
+ * Sec. 3.2 (one scale per row of A and per column of B); GLOBAL is the matrix-wide scale of
+ * Sec. 2.3 / Eq. getlambda (a_max over the whole matrix), the setting of the paper's worked
+ * 3x3 example.  Residual codes keep one scale per vector in both modes. */
+typedef enum srq_scale_t { SRQ_SCALE_VECTOR = 0, SRQ_SCALE_GLOBAL = 1 } srq_scale_t;
+
 typedef struct srq_context* srq_handle_t;
 
 /* Statistics written to device memory by srq_compensated_gemm. */
@@ -117,6 +123,12 @@ srq_status_t srq_workspace_bytes(int64_t M, int64_t N, int64_t K, double max_den
  * same problem is always enough). */
 srq_status_t srq_set_workspace(srq_handle_t handle, void* workspace, size_t bytes);
 srq_status_t srq_stage_workspace_bytes(int64_t M, int64_t N, int64_t K, size_t* bytes);
+
+/* Selects the scale granularity (see srq_scale_t) that later srq_compensated_gemm calls on
+ * this handle use; a new handle starts with SRQ_SCALE_VECTOR.  With SRQ_SCALE_GLOBAL the
+ * exported s_a / lam_a / s_b / lam_b vectors hold the one matrix-wide value in every entry.
+ * Host call; returns SRQ_STATUS_INVALID_ARG for an unknown mode. */
+srq_status_t srq_set_scale_mode(srq_handle_t handle, srq_scale_t mode);
 
 /* Stage timing of srq_compensated_gemm (the per-stage time shares of Sec. 4.1.2).  When
  * enabled, the call records a pair of HIP events on `stream` around each stage;

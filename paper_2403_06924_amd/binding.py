@@ -20,12 +20,13 @@ AXIS_ROW, AXIS_COL = 0, 1
 LAYOUT_VECTOR_MAJOR, LAYOUT_ELEMENT_MAJOR = 0, 1
 ROUND_NEAREST_EVEN, ROUND_TRUNC = 0, 1
 STRATEGY_AUTO, STRATEGY_CSR_VALU, STRATEGY_CSR_MFMA = 0, 1, 2
+SCALE_VECTOR, SCALE_GLOBAL = 0, 1
 
 EXPORTS = [
     "srq_create", "srq_destroy", "srq_workspace_bytes", "srq_set_workspace",
     "srq_stage_workspace_bytes", "srq_last_hip_error", "srq_status_string", "srq_quantize",
     "srq_build_sparse_residual", "srq_gemm_i8", "srq_spmm_accumulate", "srq_compensated_gemm",
-    "srq_get_intermediates", "srq_profile_enable", "srq_profile_read",
+    "srq_get_intermediates", "srq_profile_enable", "srq_profile_read", "srq_set_scale_mode",
 ]
 STAGES = ["quantize", "gemm", "select", "residual", "term1_prep", "term1", "term2_prep", "term2"]
 
@@ -84,6 +85,7 @@ def load():
                                          f32, f32, vp, i64, vp, i64, vp, C.POINTER(Debug), vp]
     lib.srq_get_intermediates.argtypes = [vp, C.POINTER(Intermediates)]
     lib.srq_profile_enable.argtypes = [vp, i32]
+    lib.srq_set_scale_mode.argtypes = [vp, i32]
     lib.srq_profile_read.argtypes = [vp, C.POINTER(f32)]
     for name in EXPORTS:
         if name != "srq_status_string":
@@ -174,6 +176,10 @@ class Srq:
         off = ptr - self.ws.data_ptr()
         nbytes = count * torch.empty((), dtype=dtype).element_size()
         return self.ws[off:off + nbytes].view(dtype)
+
+    def set_scale_mode(self, mode):
+        """srq_set_scale_mode: SCALE_VECTOR (default) or SCALE_GLOBAL for later compensated_gemm calls."""
+        self._ret(self.lib.srq_set_scale_mode(self.h, int(mode)), "srq_set_scale_mode")
 
     def profile_enable(self, on=True):
         self._ret(self.lib.srq_profile_enable(self.h, 1 if on else 0), "srq_profile_enable")

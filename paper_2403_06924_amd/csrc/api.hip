@@ -193,6 +193,12 @@ srq_status_t srq_create(srq_handle_t* handle, int device) {
   return SRQ_STATUS_OK;
 }
 
+srq_status_t srq_set_scale_mode(srq_handle_t h, srq_scale_t mode) {
+  if (!h || (mode != SRQ_SCALE_VECTOR && mode != SRQ_SCALE_GLOBAL)) return SRQ_STATUS_INVALID_ARG;
+  h->scale_mode = (int)mode;
+  return SRQ_STATUS_OK;
+}
+
 srq_status_t srq_profile_enable(srq_handle_t h, int enable) {
   if (!h) return SRQ_STATUS_INVALID_ARG;
   if (enable && !h->prof_created) {
@@ -486,8 +492,11 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   im.A_int = p.A_int; im.B_int = p.B_int; im.s_a = p.s_a; im.lam_a = p.lam_a; im.s_b = p.s_b; im.lam_b = p.lam_b;
 
   h->prof_used = 0;
-  const bool fastA = K > 0 && rows_fused_ok(A, K, lda, p.A_int, K, p.RA_int, K);
-  const bool fastB = K > 0 && cols_pass_ok(B, N, ldb);
+  // the one-pass kernels derive each vector's scale from the data they hold; a matrix-wide
+  // scale needs all maxima first and takes the staged kernels
+  const bool global_scale = h->scale_mode == SRQ_SCALE_GLOBAL;
+  const bool fastA = K > 0 && !global_scale && rows_fused_ok(A, K, lda, p.A_int, K, p.RA_int, K);
+  const bool fastB = K > 0 && !global_scale && cols_pass_ok(B, N, ldb);
   bool ra_vm_done = false, rb_vm_done = false, rb_em_done = false;
   // lines 1: Quant.  amax per vector -> scale, lambda -> codes (and max |residual| per vector)
   {
@@ -501,6 +510,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_a), M, 0, st));
     if (comp) SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_ra), M, 0, st));
     SRQ_HIP(h, launch_amax(A, M, K, lda, SRQ_AXIS_ROW, reinterpret_cast<uint32_t*>(p.s_a), st));
+    if (global_scale) SRQ_HIP(h, launch_broadcast_max(reinterpret_cast<uint32_t*>(p.s_a), M, st));
     SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_a), p.lam_a, M, qmax, st));
     SRQ_HIP(h, launch_quantize_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, qmax, trunc,
                                      SRQ_LAYOUT_VECTOR_MAJOR, p.A_int, K,
@@ -527,6 +537,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     }
   } else {
     SRQ_HIP(h, launch_amax(B, K, N, ldb, SRQ_AXIS_COL, reinterpret_cast<uint32_t*>(p.s_b), st));
+    if (global_scale) SRQ_HIP(h, launch_broadcast_max(reinterpret_cast<uint32_t*>(p.s_b), N, st));
     SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_b), p.lam_b, N, qmax, st));
     SRQ_HIP(h, launch_quantize_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, qmax, trunc,
                                      SRQ_LAYOUT_VECTOR_MAJOR, p.B_int, K,

@@ -52,6 +52,24 @@ __global__ __launch_bounds__(256) void amax_cols_kernel(const float* __restrict_
   atomicMax(&amax_bits[c], __float_as_uint(m));
 }
 
+// Matrix-wide scale (Eq. getlambda's a_max over the whole matrix): one block replaces every
+// per-vector maximum by the maximum over all vectors.  The patterns are those of
+// non-negative floats, which order like unsigned integers.
+__global__ __launch_bounds__(1024) void broadcast_max_kernel(uint32_t* bits, int64_t n) {
+  __shared__ uint32_t sm[16];
+  uint32_t m = 0;
+  for (int64_t i = threadIdx.x; i < n; i += 1024) m = bits[i] > m ? bits[i] : m;
+  for (int off = 32; off > 0; off >>= 1) {
+    uint32_t y = __shfl_xor(m, off, 64);
+    m = y > m ? y : m;
+  }
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = 0;
+  for (int i = 0; i < 16; ++i) m = sm[i] > m ? sm[i] : m;
+  for (int64_t i = threadIdx.x; i < n; i += 1024) bits[i] = m;
+}
+
 __global__ void scales_kernel(uint32_t* amax_bits_then_scale, float* lambda, int64_t nvec, float qmax) {
   int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (v >= nvec) return;
@@ -222,6 +240,12 @@ hipError_t launch_scales(uint32_t* amax_bits_then_scale, float* lambda, int64_t 
   if (nvec <= 0) return hipSuccess;
   hipLaunchKernelGGL(scales_kernel, dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st,
                      amax_bits_then_scale, lambda, nvec, (float)qmax);
+  return hipGetLastError();
+}
+
+hipError_t launch_broadcast_max(uint32_t* bits, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(broadcast_max_kernel, dim3(1), dim3(1024), 0, st, bits, n);
   return hipGetLastError();
 }
 

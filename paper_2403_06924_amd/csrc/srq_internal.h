@@ -18,6 +18,7 @@ struct srq_context {
   unsigned prof_used;                       // bit i: stage i ran in the last call
   hipEvent_t prof_ev[2 * SRQ_NUM_STAGES];   // start/stop per stage, created on enable
   int prof_created;
+  int scale_mode;        // srq_scale_t of the next srq_compensated_gemm calls
 };
 
 namespace srq {
@@ -53,6 +54,8 @@ hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
 hipError_t launch_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
                        uint32_t* amax_bits, hipStream_t st);
 // in place: amax bits -> scale = amax/qmax; lambda = qmax/amax (lambda may be null)
+// every entry of the vector of non-negative float bit patterns becomes their maximum
+hipError_t launch_broadcast_max(uint32_t* bits, int64_t n, hipStream_t st);
 hipError_t launch_scales(uint32_t* amax_bits_then_scale, float* lambda, int64_t nvec, int qmax,
                          hipStream_t st);
 // codes of X in `layout`; if ramax_bits != null also accumulates max|residual| per vector

@@ -1,7 +1,8 @@
 """Precision sweep on the GPU: the paper's five input distributions at 1024^2, INT8 and INT4
 (Sec. 4.1.1, caption of the precision figure), with the direct quantization ("origin",
 theta = inf), the compensation with unreduced operands ("full", theta = 0) and the sparse
-compensation over a sweep of densities.
+compensation over a sweep of densities; "full, global scale" is the unreduced compensation under
+one matrix-wide first-level scale per operand (Sec. 2.3), the setting of the paper's "Full" curve.
 
     python -m paper_2403_06924_amd.precision_sweep [--size 1024] [--seed 7]
 
@@ -50,8 +51,8 @@ def sweep(size, seed, bits_list=(8, 4), kinds=KINDS, densities=DENSITIES, out=pr
     rows = []
     for bits in bits_list:
         out("\n### INT%d, %d x %d x %d, seed %d\n" % (bits, size, size, size, seed))
-        out("| distribution | origin | full | " + " | ".join("d=%.2f" % d for d in densities) + " |")
-        out("|---|---|---|" + "---|" * len(densities))
+        out("| distribution | origin | full | full, global scale | " + " | ".join("d=%.2f" % d for d in densities) + " |")
+        out("|---|---|---|---|" + "---|" * len(densities))
         for kind in kinds:
             A = torch.from_numpy(wl.paper_distribution(kind, (size, size), seed)).cuda()
             B = torch.from_numpy(wl.paper_distribution(kind, (size, size), seed + 1)).cuda()
@@ -61,6 +62,10 @@ def sweep(size, seed, bits_list=(8, 4), kinds=KINDS, densities=DENSITIES, out=pr
             e_origin = rel_err(torch, C64, C)
             C, _, _ = h.compensated_gemm(A, B, 0.0, 0.0, bits=bits, dense_fallback_density=0.0)
             e_full = rel_err(torch, C64, C)
+            h.set_scale_mode(b.SCALE_GLOBAL)        # the matrix-wide scale of the paper's earlier method
+            C, _, _ = h.compensated_gemm(A, B, 0.0, 0.0, bits=bits, dense_fallback_density=0.0)
+            e_full_global = rel_err(torch, C64, C)
+            h.set_scale_mode(b.SCALE_VECTOR)
             Qa, sa, _ = h.quantize(A, b.AXIS_ROW, bits=bits)
             Qb, sb, _ = h.quantize(B, b.AXIS_COL, bits=bits)
             _, _, drow, dcol = h.gemm_i8(Qa, sa, Qb, sb)
@@ -76,9 +81,9 @@ def sweep(size, seed, bits_list=(8, 4), kinds=KINDS, densities=DENSITIES, out=pr
                 rows.append({"bits": bits, "kind": kind, "target_density": d,
                              "density_a": st["nnz_a"] / (size * size), "density_b": st["nnz_b"] / (size * size),
                              "theta_a": ta, "theta_b": tb, "th_2mean": th2, "err": e,
-                             "err_origin": e_origin, "err_full": e_full})
+                             "err_origin": e_origin, "err_full": e_full, "err_full_global": e_full_global})
                 cells.append("%.2e (Th %.2f)" % (e, th2))
-            out("| %s | %.2e | %.2e | %s |" % (kind, e_origin, e_full, " | ".join(cells)))
+            out("| %s | %.2e | %.2e | %.2e | %s |" % (kind, e_origin, e_full, e_full_global, " | ".join(cells)))
     h.close()
     return rows
 

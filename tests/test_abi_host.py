@@ -164,6 +164,10 @@ def test_staged_entry_points_validation(dry):
     assert bs(Rq=None, rscale=None) == b.NO_DEVICE             # selection only
     assert bs(cap=-1) == b.INVALID_ARG
     assert bs(cap=2 ** 31) == b.INVALID_ARG
+    assert lib.srq_set_scale_mode(h, b.SCALE_GLOBAL) == b.OK
+    assert lib.srq_set_scale_mode(h, 7) == b.INVALID_ARG
+    assert lib.srq_set_scale_mode(None, b.SCALE_VECTOR) == b.INVALID_ARG
+    assert lib.srq_set_scale_mode(h, b.SCALE_VECTOR) == b.OK
 
 
 def test_missing_library_fails_loudly(monkeypatch, lib):

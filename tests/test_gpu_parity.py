@@ -232,7 +232,7 @@ def test_spmm_tiled_kernel_bit_exact(srq, b, shape, side, density, want_int):
 
 # ------------------------------------------------------------------ whole path
 def check_against_oracle(srq, b, A, B, theta_a, theta_b, *, bits=8, rnd=0, strategy=1, s=2.0,
-                         alpha=1.0, beta=0.0, C_in=None):
+                         alpha=1.0, beta=0.0, C_in=None, scale_mode="vector"):
     M, K = A.shape
     N = B.shape[1]
     stats = b.stats_tensor()
@@ -248,7 +248,7 @@ def check_against_oracle(srq, b, A, B, theta_a, theta_b, *, bits=8, rnd=0, strat
     t_a = host(im["t_a"]) if comp else None
     t_b = host(im["t_b"]) if comp else None
     ref = o.compensated_gemm(A, B, theta_a, theta_b, bits=bits, rounding=ROUND[rnd], alpha=alpha, beta=beta,
-                             C_in=C_in, dense_fallback_density=s,
+                             C_in=C_in, dense_fallback_density=s, scale_mode=scale_mode,
                              thresh_a=t_a if comp and not np.isinf(theta_a) else None,
                              thresh_b=t_b if comp and not np.isinf(theta_b) else None)
     assert (host(im["A_int"]) == ref.A_int).all()
@@ -260,7 +260,7 @@ def check_against_oracle(srq, b, A, B, theta_a, theta_b, *, bits=8, rnd=0, strat
     if comp:
         np.testing.assert_allclose(host(im["drow"]), ref.drow, rtol=MEAN_TOL)
         np.testing.assert_allclose(host(im["dcol"]), ref.dcol, rtol=MEAN_TOL)
-        pure = o.compensated_gemm(A, B, theta_a, theta_b, bits=bits, rounding=ROUND[rnd])
+        pure = o.compensated_gemm(A, B, theta_a, theta_b, bits=bits, rounding=ROUND[rnd], scale_mode=scale_mode)
         np.testing.assert_allclose(t_a, pure.t_a, rtol=2 * MEAN_TOL)
         np.testing.assert_allclose(t_b, pure.t_b, rtol=2 * MEAN_TOL)
         assert (host(im["s_ra"]) == ref.s_ra).all() and (host(im["s_rb"]) == ref.s_rb).all()
@@ -394,3 +394,25 @@ def test_paper_distributions_1024(srq, b, kind, bits):
     C0, _, _ = srq.compensated_gemm(dev(A), dev(B), 0.0, 0.0, bits=bits, dense_fallback_density=0.0)
     ref0 = o.compensated_gemm(A, B, 0.0, bits=bits)
     assert o.error_rel(ref0.C, host(C0)) <= 1e-5
+
+
+# ------------------------------------------------------------------ matrix-wide first-level scale
+@pytest.mark.parametrize("shape", [(256, 256, 256), (257, 129, 511)])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_global_scale_mode(srq, b, shape, bits):
+    """One scale for the whole of A and one for the whole of B (Sec. 2.3, Eq. getlambda; the
+    setting of the worked 3x3 example), residual codes still per vector: every stage against
+    the oracle's global mode, and the handle returns to vector-wise scales afterwards."""
+    M, N, K = shape
+    rng = np.random.default_rng(M + N + K + bits)
+    A = (rng.standard_normal((M, K)) * np.exp(rng.standard_normal((M, 1)))).astype(F32)
+    B = (rng.standard_normal((K, N)) * np.exp(rng.standard_normal((1, N)))).astype(F32)
+    srq.set_scale_mode(b.SCALE_GLOBAL)
+    try:
+        ref, C, st = check_against_oracle(srq, b, A, B, 0.05, 0.05, bits=bits, strategy=0, scale_mode="global")
+        assert len(np.unique(ref.s_a)) == 1 and len(np.unique(ref.s_b)) == 1
+        ref0, _, _ = check_against_oracle(srq, b, A, B, 0.0, 0.0, bits=bits, strategy=2, s=0.0, scale_mode="global")
+    finally:
+        srq.set_scale_mode(b.SCALE_VECTOR)
+    refv, _, _ = check_against_oracle(srq, b, A, B, 0.05, 0.05, bits=bits, strategy=0)
+    assert len(np.unique(refv.s_a)) > 1
