@@ -219,6 +219,24 @@ def main():
                 "dense_compensated_ms": ms_full, "dense_compensated_tops": ops / (ms_full * 1e-3) / 1e12,
                 "prequantized_ms": sum(v for k, v in stage_ms.items() if k not in ("quantize", "residual"))}
 
+    # the streaming stages against the HBM peak, on their algorithmic bytes: a1 + a5 read each
+    # FP32 element once and write its code and its residual code; a6 reads each FP32 element
+    # once more and writes 5 bytes per kept entry plus one pointer per vector
+    PEAK_HBM_GBS = 8000.0
+    q_bytes = 6.0 * (M * K + K * N) + 16.0 * (M + N)
+    s_bytes = 4.0 * (M * K + K * N) + 5.0 * (st["nnz_a"] + st["nnz_b"]) + 4.0 * (M + N + 2)
+    q_ms = stage_ms["quantize"] + stage_ms["residual"]
+    stage_rooflines = {
+        "quantize+residual": {"bound": "hbm", "algorithmic_bytes": q_bytes,
+                              "achieved": q_bytes / (q_ms * 1e-3) / 1e9 if q_ms > 0 else None,
+                              "peak": PEAK_HBM_GBS, "unit": "GB/s"},
+        "select": {"bound": "hbm", "algorithmic_bytes": s_bytes,
+                   "achieved": s_bytes / (stage_ms["select"] * 1e-3) / 1e9 if stage_ms["select"] > 0 else None,
+                   "peak": PEAK_HBM_GBS, "unit": "GB/s"},
+    }
+    for r in stage_rooflines.values():
+        r["frac"] = r["achieved"] / r["peak"] if r["achieved"] else None
+
     out = {
         "metric": "effective TOPS (2MNK/s) of compensated INT8 GEMM", "value": value, "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -234,6 +252,7 @@ def main():
         "stage_ms": stage_ms,
         "variants": variants,
         "roofline": roof,
+        "stage_rooflines": stage_rooflines,
         "accuracy": accuracy,
     }
     if not args.no_cpu_baseline:

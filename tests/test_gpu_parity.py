@@ -416,3 +416,50 @@ def test_global_scale_mode(srq, b, shape, bits):
         srq.set_scale_mode(b.SCALE_VECTOR)
     refv, _, _ = check_against_oracle(srq, b, A, B, 0.05, 0.05, bits=bits, strategy=0)
     assert len(np.unique(refv.s_a)) > 1
+
+
+# ------------------------------------------------------------------ degenerate inputs
+def test_degenerate_shapes_and_vectors(srq, b):
+    """Empty dimensions, K = 0, a 1x1x1 problem, all-zero operands and zero vectors
+    (amax = 0 gives scale 0, lambda 0 and zero codes)."""
+    rng = np.random.default_rng(5)
+    # M = 0 / N = 0: nothing to write, status OK
+    for M, N, K in ((0, 8, 8), (8, 0, 8)):
+        C, _, _ = srq.compensated_gemm(dev(np.zeros((M, K), F32)), dev(np.zeros((K, N), F32)), 0.5, 0.5)
+        assert tuple(C.shape) == (M, N)
+    # K = 0: the product is empty, C = alpha * 0 + beta * C_in
+    Cin = rng.standard_normal((6, 7)).astype(F32)
+    C, _, _ = srq.compensated_gemm(dev(np.zeros((6, 0), F32)), dev(np.zeros((0, 7), F32)), 0.5, 0.5,
+                                   alpha=2.0, beta=0.5, C_in=dev(Cin))
+    assert (host(C) == F32(0.5) * Cin).all()
+    # 1 x 1 x 1
+    A = np.array([[0.75]], F32); B = np.array([[-1.5]], F32)
+    check_against_oracle(srq, b, A, B, 0.0, 0.0, strategy=1)
+    check_against_oracle(srq, b, A, B, 0.0, 0.0, strategy=2)
+    # all-zero A: every scale of A is 0, C = 0
+    A = np.zeros((40, 72), F32); B = rng.standard_normal((72, 24)).astype(F32)
+    ref, C, _ = check_against_oracle(srq, b, A, B, 0.3, 0.3, strategy=0)
+    assert (ref.s_a == 0).all() and (C == 0).all()
+    # zero rows of A, zero columns of B, one zero column of A and row of B
+    A = rng.standard_normal((130, 200)).astype(F32); B = rng.standard_normal((200, 70)).astype(F32)
+    A[3] = 0; A[129] = 0; A[:, 17] = 0; B[:, 0] = 0; B[:, 69] = 0; B[50] = 0
+    for strategy in (1, 2):
+        ref, C, _ = check_against_oracle(srq, b, A, B, 0.4, 0.4, strategy=strategy)
+        assert ref.s_a[3] == 0 and ref.s_b[0] == 0 and (C[3] == 0).all() and (C[:, 69] == 0).all()
+
+
+def test_inner_dimension_at_the_int32_bound(srq, b):
+    """K = 133144 is the largest inner dimension whose worst-case sum K * 127^2 stays below
+    2^31; operands of constant maximum magnitude reach it.  One more is refused."""
+    K = 133144
+    M, N = 2, 3
+    A = np.full((M, K), 3.0, F32); A[1] = -3.0
+    B = np.full((K, N), 2.0, F32); B[:, 2] = -2.0
+    C, _, dbg = srq.compensated_gemm(dev(A), dev(B), float("inf"), float("inf"), debug=True)
+    D = host(dbg["D_int"]).astype(np.int64)
+    assert (np.abs(D) == K * 127 * 127).all() and K * 127 * 127 < 2 ** 31
+    ref = o.compensated_gemm(A, B, np.inf)
+    assert (host(C) == ref.C).all()
+    with pytest.raises(b.SrqError) as ei:
+        srq.compensated_gemm(dev(np.zeros((M, K + 1), F32)), dev(np.zeros((K + 1, N), F32)), 0.5, 0.5)
+    assert ei.value.status == b.K_OVERFLOW
