@@ -225,6 +225,9 @@ srq_status_t srq_spmm_accumulate(srq_handle_t handle, srq_axis_t side, srq_strat
  *   Cin                read only if beta != 0 (ldcin >= N); must not overlap C.
  *   stats_dev          device srq_stats_t, may be NULL.
  *   dbg                host pointer to a struct of device buffers, may be NULL.
+ * With a fixed strategy (CSR_VALU or CSR_MFMA) and dense_fallback_density > 1 the call only
+ * enqueues kernels on `stream`: no allocation, no host read-back, no memset node, so it may be
+ * recorded into a HIP graph by a capturing caller (the workspace must be attached before).
  * Returns SRQ_STATUS_CAPACITY (after the first product and the selection ran: C then holds the
  * uncorrected D_F, no correction term was added) when a synchronising mode finds more kept
  * entries than the workspace was sized for; in non-synchronising

@@ -187,6 +187,8 @@ srq_status_t srq_create(srq_handle_t* handle, int device) {
     if (e != hipSuccess || device >= n) { delete c; return SRQ_STATUS_HIP_ERROR; }
     e = hipSetDevice(device);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->host_nnz), 2 * sizeof(int64_t), 0);
+    int cus = 0;
+    if (e == hipSuccess) e = srq::gemm_device_cus(&cus);
     if (e != hipSuccess) { delete c; return SRQ_STATUS_HIP_ERROR; }
   }
   *handle = c;

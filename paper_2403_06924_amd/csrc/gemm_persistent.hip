@@ -302,17 +302,29 @@ bool gemm_persistent_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64
   return (M / BM) * (N / BN) >= 512;
 }
 
+// Compute units of the current device, looked up once per device (srq_create primes it, so
+// that no property query happens inside a caller's stream capture).
+hipError_t gemm_device_cus(int* cus) {
+  static int cached[64] = {0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64 || !cached[dev]) {
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) { *cus = prop.multiProcessorCount; return hipSuccess; }
+    cached[dev] = prop.multiProcessorCount;
+  }
+  *cus = cached[dev];
+  return hipSuccess;
+}
+
 hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
                                      const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st) {
-  static int num_cu = 0;
-  if (!num_cu) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
-    if (e != hipSuccess) return e;
-    num_cu = prop.multiProcessorCount;
-  }
+  int num_cu = 0;
+  hipError_t e = gemm_device_cus(&num_cu);
+  if (e != hipSuccess) return e;
   const int64_t tm = M / BM, tn = N / BN;
   int64_t wgs = num_cu / 8 * 8;                              // one workgroup per CU, a multiple of the 8 XCDs
   if (wgs < 8) wgs = 8;

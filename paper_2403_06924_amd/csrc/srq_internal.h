@@ -128,6 +128,7 @@ int64_t gemm_tiles_n(int64_t M, int64_t N);
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
                           const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st);
 // persistent-workgroup variant for full, aligned, large problems (chosen inside launch_gemm_i8)
+hipError_t gemm_device_cus(int* cus);
 bool gemm_persistent_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb,
                         int64_t ldb, const GemmEpilogue& ep);
 hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
