@@ -88,12 +88,51 @@ def sweep(size, seed, bits_list=(8, 4), kinds=KINDS, densities=DENSITIES, out=pr
     return rows
 
 
+def qr_table(size, seed, bits_list=(8, 4), kinds=("chisquare", "uniform", "normal", "exponential"),
+             densities=(0.05, 0.2, 0.5), out=print):
+    """The QR experiment of Sec. 4.2: Q.R by the quantized products against the factored matrix."""
+    import torch
+    from . import binding as b
+    h = b.Srq(device=0)
+    rows = []
+    out("\n### Q.R of a Householder factorization, %d x %d, seed %d: E = ||X - Q.R||_F / ||X||_F\n" % (size, size, seed))
+    out("| distribution | bits | FP32 | origin | full | " + " | ".join("d=%.2f" % d for d in densities) + " |")
+    out("|---|---|---|---|---|" + "---|" * len(densities))
+    for kind in kinds:
+        X, Qh, Rh = wl.qr_factors(kind, size, seed)
+        X64 = torch.from_numpy(X).cuda().double()
+        Q, R = torch.from_numpy(Qh).cuda(), torch.from_numpy(Rh).cuda()
+        e_fp32 = rel_err(torch, X64, Q @ R)
+        for bits in bits_list:
+            inf = float("inf")
+            C, _, _ = h.compensated_gemm(Q, R, inf, inf, bits=bits)
+            e_origin = rel_err(torch, X64, C)
+            C, _, _ = h.compensated_gemm(Q, R, 0.0, 0.0, bits=bits, dense_fallback_density=0.0)
+            e_full = rel_err(torch, X64, C)
+            Qa, sa, _ = h.quantize(Q, b.AXIS_ROW, bits=bits)
+            Qb, sb, _ = h.quantize(R, b.AXIS_COL, bits=bits)
+            _, _, drow, dcol = h.gemm_i8(Qa, sa, Qb, sb)
+            cells = []
+            for d in densities:
+                ta, tb = calibrate(torch, Q, drow, 0, d), calibrate(torch, R, dcol, 1, d)
+                C, _, _ = h.compensated_gemm(Q, R, ta, tb, bits=bits)
+                cells.append(rel_err(torch, X64, C))
+            rows.append((kind, bits, e_fp32, e_origin, e_full, cells))
+            out("| %s | %d | %.2e | %.2e | %.2e | %s |" % (kind, bits, e_fp32, e_origin, e_full,
+                                                          " | ".join("%.2e" % c for c in cells)))
+    h.close()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--size", type=int, default=1024)
     ap.add_argument("--seed", type=int, default=7)
+    ap.add_argument("--qr", action="store_true", help="also run the Q.R experiment of Sec. 4.2")
     args = ap.parse_args()
     sweep(args.size, args.seed)
+    if args.qr:
+        qr_table(args.size, args.seed)
 
 
 if __name__ == "__main__":

@@ -110,6 +110,16 @@ def paper_distribution(kind: str, shape, seed: int):
     return np.ascontiguousarray(X.astype(np.float32))
 
 
+def qr_factors(kind: str, n: int, seed: int):
+    """Inputs of the paper's QR experiment (Sec. 4.2): a square matrix drawn from one of the
+    precision-test distributions and its Householder QR factors, all float32.  The experiment
+    multiplies Q by R with the quantized product and compares with the matrix itself.
+    Returns (X, Q, R) with Q orthogonal (n x n) and R upper triangular."""
+    X = paper_distribution(kind, (n, n), seed)
+    Q, R = np.linalg.qr(X.astype(np.float64))
+    return X, np.ascontiguousarray(Q.astype(np.float32)), np.ascontiguousarray(R.astype(np.float32))
+
+
 def theta_for_density(X, dvec, axis: str, density: float) -> float:
     """Harness-side calibration: the threshold factor theta such that about
     ``density`` of the entries of X satisfy |x| > theta * dvec[v].

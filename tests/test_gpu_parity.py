@@ -463,3 +463,24 @@ def test_inner_dimension_at_the_int32_bound(srq, b):
     with pytest.raises(b.SrqError) as ei:
         srq.compensated_gemm(dev(np.zeros((M, K + 1), F32)), dev(np.zeros((K + 1, N), F32)), 0.5, 0.5)
     assert ei.value.status == b.K_OVERFLOW
+
+
+# ------------------------------------------------------------------ the QR experiment's operands
+@pytest.mark.parametrize("kind", ["chisquare", "uniform", "normal", "exponential"])
+def test_qr_factors_product(srq, b, kind):
+    """Sec. 4.2 multiplies the Householder factors Q (orthogonal) and R (upper triangular, so
+    half of every column is zero) with the compensated product: every stage against the
+    oracle, all three strategies, and the error against the factored matrix falls from the
+    direct quantization to the sparse compensation to the unreduced one."""
+    n = 384
+    X, Q, R = wl.qr_factors(kind, n, 31)
+    plain = o.quantized_product(Q, R)
+    drow, dcol = o.abs_means(plain.D_F)
+    ta = wl.theta_for_density(Q, drow, "row", 0.3)
+    tb = wl.theta_for_density(R, dcol, "col", 0.3)
+    for strategy in (0, 1, 2):
+        ref, C, st = check_against_oracle(srq, b, Q, R, ta, tb, strategy=strategy)
+    full = o.compensated_gemm(Q, R, 0.0)
+    X64 = X.astype(np.float64)
+    e_origin, e_sparse, e_full = (o.error_rel(X64, plain.D_F), o.error_rel(X64, ref.C), o.error_rel(X64, full.C))
+    assert e_origin > e_sparse > e_full
