@@ -187,7 +187,10 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
       int* dst = tile + (w * kVecPerWave + q) * LDT + lane * LE;
 #pragma unroll
       for (int t = 0; t < LE; ++t) dst[t] = acc[t];
-    } else if (v < nvec && lane_in) {
+    } else if (v < nvec && lane_in &&
+               (ep.final_scale || ep.D_int ||
+                __builtin_amdgcn_readlane(pl, q) != __builtin_amdgcn_readlane(pl, q + 1))) {
+      // (a row without kept entries leaves C as it is unless this pass also applies alpha / beta)
       const float sr = ep.s_row[v];
       float* c = ep.C + v * ep.ldc + e0;
       if (cvec) {                                    // 16-byte accesses: C, s_col (and Cin) are aligned

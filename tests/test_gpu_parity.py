@@ -484,3 +484,32 @@ def test_qr_factors_product(srq, b, kind):
     X64 = X.astype(np.float64)
     e_origin, e_sparse, e_full = (o.error_rel(X64, plain.D_F), o.error_rel(X64, ref.C), o.error_rel(X64, full.C))
     assert e_origin > e_sparse > e_full
+
+
+# ------------------------------------------------------------------ leading dimensions
+@pytest.mark.parametrize("pad", [(0, 0, 0, 0), (16, 32, 64, 4), (3, 5, 7, 1)])
+@pytest.mark.parametrize("strategy", [1, 2])
+def test_leading_dimensions(srq, b, pad, strategy):
+    """A, B, C and C_in as windows of wider allocations: aligned paddings keep the streaming
+    kernels, odd ones fall to the generic kernels; the result is the same bits either way and
+    nothing outside the window of C is touched."""
+    M, N, K = 192, 320, 256
+    rng = np.random.default_rng(17)
+    A = rng.standard_normal((M, K)).astype(F32); B = rng.standard_normal((K, N)).astype(F32)
+    Cin = rng.standard_normal((M, N)).astype(F32)
+    pa, pb, pc, pi = pad
+    Abig = torch.full((M, K + pa), 7.0, device="cuda"); Abig[:, :K] = dev(A)
+    Bbig = torch.full((K, N + pb), 7.0, device="cuda"); Bbig[:, :N] = dev(B)
+    Cbig = torch.full((M, N + pc), -5.0, device="cuda")
+    Ibig = torch.full((M, N + pi), 9.0, device="cuda"); Ibig[:, :N] = dev(Cin)
+    theta = 2.0 / (0.8 * K ** 0.5)
+    srq.compensated_gemm(Abig[:, :K], Bbig[:, :N], theta, theta, strategy=strategy, alpha=0.5, beta=2.0,
+                         C_in=Ibig[:, :N], out=Cbig[:, :N])
+    torch.cuda.synchronize()
+    C0, _, _ = srq.compensated_gemm(dev(A), dev(B), theta, theta, strategy=strategy, alpha=0.5, beta=2.0,
+                                    C_in=dev(Cin))
+    assert torch.equal(Cbig[:, :N], C0)
+    if pc:
+        assert (Cbig[:, N:] == -5.0).all()
+    ref = o.compensated_gemm(A, B, theta, theta, alpha=0.5, beta=2.0, C_in=Cin)
+    assert rel_fro(ref.C, host(C0)) <= REL_TOL
