@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--dense-fallback", type=float, default=2.0, help="Algorithm 1's limit s (>1: off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the timing of the plain (theta=inf) and unreduced (theta=0) variants")
     ap.add_argument("--report", default=None, help="also write the full report to this JSON file")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (reference point for the FETCH_SIZE / "
@@ -212,12 +214,14 @@ def main():
             fn()
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / reps * 1e3
-    inf = float("inf")
-    ms_plain = timed(lambda: h.compensated_gemm(Ad, Bd, inf, inf, out=Cd))
-    ms_full = timed(lambda: h.compensated_gemm(Ad, Bd, 0.0, 0.0, dense_fallback_density=0.0, out=Cd))
-    variants = {"plain_int8_ms": ms_plain, "plain_int8_tops": ops / (ms_plain * 1e-3) / 1e12,
-                "dense_compensated_ms": ms_full, "dense_compensated_tops": ops / (ms_full * 1e-3) / 1e12,
-                "prequantized_ms": sum(v for k, v in stage_ms.items() if k not in ("quantize", "residual"))}
+    variants = None
+    if not args.no_variants:
+        inf = float("inf")
+        ms_plain = timed(lambda: h.compensated_gemm(Ad, Bd, inf, inf, out=Cd))
+        ms_full = timed(lambda: h.compensated_gemm(Ad, Bd, 0.0, 0.0, dense_fallback_density=0.0, out=Cd))
+        variants = {"plain_int8_ms": ms_plain, "plain_int8_tops": ops / (ms_plain * 1e-3) / 1e12,
+                    "dense_compensated_ms": ms_full, "dense_compensated_tops": ops / (ms_full * 1e-3) / 1e12,
+                    "prequantized_ms": sum(v for k, v in stage_ms.items() if k not in ("quantize", "residual"))}
 
     # the streaming stages against the HBM peak, on their algorithmic bytes: a1 + a5 read each
     # FP32 element once and write its code and its residual code; a6 reads each FP32 element

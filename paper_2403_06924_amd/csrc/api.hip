@@ -300,15 +300,31 @@ srq_status_t srq_quantize(srq_handle_t h, const float* X, int64_t rows, int64_t 
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   int qmax = qmax_of_bits(bits);
   if (nvec == 0) return SRQ_STATUS_OK;
+  const int trunc = round == SRQ_ROUND_TRUNC;
+  // streaming kernels for aligned operands: rows in one pass, columns in two
+  if (rows > 0 && cols > 0 && axis == SRQ_AXIS_ROW && layout == SRQ_LAYOUT_VECTOR_MAJOR &&
+      rows_fused_ok(X, cols, ldx, Q, ldq, nullptr, 0)) {
+    SRQ_HIP(h, launch_rows_fused(X, rows, cols, ldx, qmax, trunc, Q, ldq, scale, lam, nullptr, 0, nullptr,
+                                 nullptr, st));
+    return SRQ_STATUS_OK;
+  }
   SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(scale), nvec, 0, st));
   if (rows == 0 || cols == 0) {
     if (lambda) SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(lambda), nvec, 0, st));
     return SRQ_STATUS_OK;
   }
+  if (axis == SRQ_AXIS_COL && cols_pass_ok(X, cols, ldx)) {
+    const bool vm = layout == SRQ_LAYOUT_VECTOR_MAJOR;
+    SRQ_HIP(h, launch_cols_amax(X, rows, cols, ldx, reinterpret_cast<uint32_t*>(scale), st));
+    SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(scale), lam, nvec, qmax, st));
+    SRQ_HIP(h, launch_cols_codes(X, rows, cols, ldx, qmax, trunc, scale, lam, vm ? Q : nullptr, ldq,
+                                 vm ? nullptr : Q, ldq, nullptr, st));
+    return SRQ_STATUS_OK;
+  }
   SRQ_HIP(h, launch_amax(X, rows, cols, ldx, axis, reinterpret_cast<uint32_t*>(scale), st));
   SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(scale), lam, nvec, qmax, st));
-  SRQ_HIP(h, launch_quantize_tiles(X, rows, cols, ldx, axis, scale, lam, qmax, round == SRQ_ROUND_TRUNC,
-                                   layout, Q, ldq, nullptr, st));
+  SRQ_HIP(h, launch_quantize_tiles(X, rows, cols, ldx, axis, scale, lam, qmax, trunc, layout, Q, ldq, nullptr,
+                                   st));
   return SRQ_STATUS_OK;
 }
 
