@@ -547,7 +547,12 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_rb), p.lam_rb, N, qmax, st));
       // the K-contiguous residual codes feed the matrix-core paths; the k-major copy is only
       // written now if the caller has fixed the vector-ALU path for term 1
-      const bool want_em = term_a && strategy == SRQ_STRATEGY_CSR_VALU && dense_fallback_density > 1.f;
+      // (or, with SRQ_STRATEGY_AUTO, if the previous call on this handle ended up there: repeated
+      // calls at a similar density then write the layout they need here and not in a second pass;
+      // a wrong guess only costs that second pass)
+      const bool want_em = term_a && dense_fallback_density > 1.f &&
+                           (strategy == SRQ_STRATEGY_CSR_VALU ||
+                            (strategy == SRQ_STRATEGY_AUTO && h->last_path_a == SRQ_STRATEGY_CSR_VALU));
       SRQ_HIP(h, launch_cols_resid(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.lam_rb,
                                    want_em ? nullptr : p.RB_int, K, want_em ? p.RB_em : nullptr, N, st));
       rb_vm_done = !want_em;
@@ -622,6 +627,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       };
       if (term_a) path_a = pick(da, kAutoMfmaDensityA);
       if (term_b) path_b = pick(db, kAutoMfmaDensityB);
+      if (term_a && strategy == SRQ_STRATEGY_AUTO) h->last_path_a = path_a;
     } else {
       if (term_a) path_a = (int)strategy;
       if (term_b) path_b = (int)strategy;

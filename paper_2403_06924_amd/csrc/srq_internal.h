@@ -19,6 +19,7 @@ struct srq_context {
   hipEvent_t prof_ev[2 * SRQ_NUM_STAGES];   // start/stop per stage, created on enable
   int prof_created;
   int scale_mode;        // srq_scale_t of the next srq_compensated_gemm calls
+  int last_path_a;       // execution SRQ_STRATEGY_AUTO chose for term 1 in the previous call (0: none yet)
 };
 
 namespace srq {
