@@ -181,3 +181,34 @@ def test_c4_rectangular_sampled(srq, b):
 @pytest.mark.parametrize("density", [0.05, 0.50])
 def test_c5_wide_range_sampled(srq, b, density):
     sampled_check(srq, b, "C5", density, 48, seed=13)
+
+
+@pytest.mark.parametrize("shape", [(5888, 5888, 384), (2560, 13312, 640)])
+def test_persistent_gemm_uneven_tile_counts(srq, b, shape):
+    """529 and 520 tiles of 256 x 256 on 256 compute units: workgroups of the persistent kernel
+    get different numbers of tiles, and the load cursor runs ahead across tile boundaries.
+    First mode (with the means) and accumulate mode (through the expanded sparse operand),
+    element by element."""
+    M, N, K = shape
+    rng = np.random.default_rng(M + N + K)
+    Qa = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    Qb = rng.integers(-127, 128, size=(N, K)).astype(np.int8)
+    sa = rng.random(M).astype(F32) + F32(0.01)
+    sb = rng.random(N).astype(F32) + F32(0.01)
+    dQa, dQb, dsa, dsb = (torch.from_numpy(x).cuda() for x in (Qa, Qb, sa, sb))
+    D_F, _, drow, dcol = srq.gemm_i8(dQa, dsa, dQb, dsb)
+    ref_int = o.int_matmul(Qa, Qb.T)
+    ref_F = o.dequant_product(ref_int, sa, sb)
+    assert (host(D_F) == ref_F).all()
+    r_row, r_col = o.abs_means(ref_F)
+    np.testing.assert_allclose(host(drow), r_row, rtol=MEAN_TOL)
+    np.testing.assert_allclose(host(dcol), r_col, rtol=MEAN_TOL)
+    # accumulate mode: C += (sparse rows of Qa) . Qb^T with 3 % of the entries kept
+    mask = rng.random((M, K)) < 0.03
+    c = o.compress(mask, Qa, "row")
+    C0 = rng.standard_normal((M, N)).astype(F32)
+    Cd = torch.from_numpy(C0).cuda()
+    srq.spmm_accumulate(0, b.STRATEGY_CSR_MFMA, M, N, K, torch.from_numpy(c.ptr).cuda(),
+                        torch.from_numpy(c.idx).cuda(), torch.from_numpy(c.val).cuda(), dQb, dsa, dsb, Cd)
+    ref_C = C0 + o.dequant_product(o.int_matmul(np.where(mask, Qa, 0), Qb.T), sa, sb)
+    assert (host(Cd) == ref_C).all()
