@@ -43,7 +43,7 @@ extern "C" {
 typedef enum srq_status_t {
   SRQ_STATUS_OK = 0,
   SRQ_STATUS_INVALID_ARG = 1,   /* null pointer, negative size, ld too small, bad enum     */
-  SRQ_STATUS_UNSUPPORTED = 2,   /* bits outside 2..8                                        */
+  SRQ_STATUS_UNSUPPORTED = 2,   /* bits outside 2..8; reduced operand of 2^31 or more elements */
   SRQ_STATUS_K_OVERFLOW = 3,    /* K * qmax^2 >= 2^31                                       */
   SRQ_STATUS_CAPACITY = 4,      /* compressed-storage capacity too small for the selection  */
   SRQ_STATUS_WORKSPACE = 5,     /* no workspace attached, or too small                      */
@@ -225,6 +225,8 @@ srq_status_t srq_spmm_accumulate(srq_handle_t handle, srq_axis_t side, srq_strat
  *   Cin                read only if beta != 0 (ldcin >= N); must not overlap C.
  *   stats_dev          device srq_stats_t, may be NULL.
  *   dbg                host pointer to a struct of device buffers, may be NULL.
+ * An operand that is reduced (finite theta) must have fewer than 2^31 elements (INT32 row
+ * pointers): SRQ_STATUS_UNSUPPORTED otherwise.
  * With a fixed strategy (CSR_VALU or CSR_MFMA) and dense_fallback_density > 1 the call only
  * enqueues kernels on `stream`: no allocation, no host read-back, no memset node, so it may be
  * recorded into a HIP graph by a capturing caller (the workspace must be attached before).

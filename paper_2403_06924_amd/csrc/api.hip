@@ -487,6 +487,9 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   }
   const bool term_a = !isinf(theta_a), term_b = !isinf(theta_b);
   const bool comp = (term_a || term_b) && K > 0;
+  // row pointers of the compressed operands are INT32: an operand that could keep 2^31 entries
+  // or more is refused rather than risking a wrapped pointer
+  if (comp && ((term_a && M * K > 2147483647LL) || (term_b && N * K > 2147483647LL))) return SRQ_STATUS_UNSUPPORTED;
   Plan p;
   memset(&p, 0, sizeof(p));
   plan_fixed(nullptr, M, N, K, &p);

@@ -117,6 +117,9 @@ def test_compensated_gemm_validation(dry):
     assert _cg(dry, beta=1.0) == b.INVALID_ARG                  # beta needs Cin
     assert _cg(dry, beta=1.0, Cin=FAKE, ldcin=64) == b.NO_DEVICE
     assert _cg(dry, ta=float("inf"), tb=float("inf")) == b.NO_DEVICE
+    # a reduced operand of 2^31 or more elements could wrap the INT32 row pointers
+    assert _cg(dry, M=65536, K=32768, lda=32768) == b.UNSUPPORTED
+    assert _cg(dry, M=65536, K=32768, lda=32768, ta=float("inf")) != b.UNSUPPORTED
     # K bound: 133144 is the largest K for 8 bits; 4-bit codes allow far more
     big = 133145
     assert _cg(dry, K=big, lda=big) == b.K_OVERFLOW
