@@ -345,6 +345,7 @@ srq_status_t srq_build_sparse_residual(srq_handle_t h, const float* X, int64_t r
   if (do_res && (!Rq || !rscale)) return SRQ_STATUS_INVALID_ARG;
   if (do_sel && (!ptr || !thresh || capacity < 0 || (capacity > 0 && (!idx || !val)))) return SRQ_STATUS_INVALID_ARG;
   if (capacity > 2147483647LL) return SRQ_STATUS_INVALID_ARG;
+  if (do_sel && rows > 0 && cols > 0 && rows > 2147483647LL / cols) return SRQ_STATUS_UNSUPPORTED;   // INT32 ptr
   int64_t nvec = axis == SRQ_AXIS_ROW ? rows : cols, veclen = axis == SRQ_AXIS_ROW ? cols : rows;
   if (rows > 0 && cols > 0) {
     if (!X || !scale || !lambda) return SRQ_STATUS_INVALID_ARG;
