@@ -368,7 +368,7 @@ hipError_t launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t
 
 // tile height / width used for an M x N problem (also sizes the partial-sum buffers)
 inline bool use_big_tiles(int64_t M, int64_t N) {
-  return ((M + 255) / 256) * ((N + 255) / 256) >= 512;
+  return ((M + 255) / 256) * ((N + 255) / 256) >= 256;   // at least one big tile per compute unit
 }
 
 }  // namespace

@@ -299,7 +299,7 @@ bool gemm_persistent_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64
   if (M <= 0 || N <= 0 || K <= 0 || (M % BM) || (N % BN) || (K % BK)) return false;
   if (((reinterpret_cast<uintptr_t>(Qa) | reinterpret_cast<uintptr_t>(Qb)) & 15) || (lda % 16) || (ldb % 16))
     return false;
-  return (M / BM) * (N / BN) >= 512;
+  return (M / BM) * (N / BN) >= 256;                        // at least one tile per compute unit
 }
 
 // Compute units of the current device, looked up once per device (srq_create primes it, so

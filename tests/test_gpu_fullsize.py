@@ -183,7 +183,7 @@ def test_c5_wide_range_sampled(srq, b, density):
     sampled_check(srq, b, "C5", density, 48, seed=13)
 
 
-@pytest.mark.parametrize("shape", [(5888, 5888, 384), (2560, 13312, 640)])
+@pytest.mark.parametrize("shape", [(5888, 5888, 384), (2560, 13312, 640), (4096, 4096, 256), (4352, 4096, 128)])
 def test_persistent_gemm_uneven_tile_counts(srq, b, shape):
     """529 and 520 tiles of 256 x 256 on 256 compute units: workgroups of the persistent kernel
     get different numbers of tiles, and the load cursor runs ahead across tile boundaries.
