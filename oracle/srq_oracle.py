@@ -338,9 +338,13 @@ def compensated_gemm(A, B, theta_a, theta_b=None, *, bits=8, rounding=ROUND_NEAR
     mask_b = select_mask(B, st.t_b, "col", signed_compare)
     st.csr_a = compress(mask_a, st.A_int, "row")
     st.csc_b = compress(mask_b, st.B_int, "col")
-    # residual products (lines 11-15), each term switching on its own density
-    st.dense_a = st.csr_a.density >= dense_fallback_density
-    st.dense_b = st.csc_b.density >= dense_fallback_density
+    # residual products (lines 11-15), each term switching on its own density.  A threshold
+    # factor of +inf means "no correction from this operand" (the plain quantized GEMM bound):
+    # that term is dropped before the density switch is looked at, whatever the limit s is.
+    skip_a = thresh_a is None and np.isinf(theta_a)
+    skip_b = thresh_b is None and np.isinf(theta_b)
+    st.dense_a = (not skip_a) and st.csr_a.density >= dense_fallback_density
+    st.dense_b = (not skip_b) and st.csc_b.density >= dense_fallback_density
     if st.dense_a:
         st.DR1_int = int_matmul(st.A_int, st.RB_int)
     else:

@@ -321,3 +321,19 @@ def test_workload_recipes_are_seeded_and_shaped():
     assert (colmax > 20).sum() == 16                           # the 16 outlier columns
     A, _ = wl.make_inputs("C5", 64, 8, 64)
     assert np.abs(A).min() >= 2.0 ** -10 and np.abs(A).max() < 2.0 ** 11
+
+
+def test_infinite_threshold_drops_the_term_before_the_density_switch():
+    """theta = +inf is the plain quantized product whatever the limit s of Algorithm 1's switch
+    is: with s = 0 ("always dense") a term whose operand keeps nothing is still dropped, and the
+    other term still takes the dense branch."""
+    rng = np.random.default_rng(3)
+    A = rng.standard_normal((20, 33)).astype(np.float32)
+    B = rng.standard_normal((33, 17)).astype(np.float32)
+    plain = o.quantized_product(A, B)
+    both = o.compensated_gemm(A, B, np.inf, np.inf, dense_fallback_density=0.0)
+    assert (both.C == plain.D_F).all() and not both.DR1_int.any() and not both.DR2_int.any()
+    one = o.compensated_gemm(A, B, 0.5, np.inf, dense_fallback_density=0.0)
+    assert one.dense_a and not one.dense_b and not one.DR2_int.any()
+    assert (one.DR1_int == o.int_matmul(one.A_int, one.RB_int)).all()
+    assert (one.C == (plain.D_F + o.dequant_product(one.DR1_int, one.s_a, one.s_rb))).all()
