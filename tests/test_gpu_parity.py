@@ -513,3 +513,47 @@ def test_leading_dimensions(srq, b, pad, strategy):
         assert (Cbig[:, N:] == -5.0).all()
     ref = o.compensated_gemm(A, B, theta, theta, alpha=0.5, beta=2.0, C_in=Cin)
     assert rel_fro(ref.C, host(C0)) <= REL_TOL
+
+
+# ------------------------------------------------------------------ randomized configurations
+@pytest.mark.parametrize("seed", [101, 102, 103])
+def test_randomized_configurations(srq, b, seed):
+    """Seeded sweep over shapes (ragged, aligned, skinny), densities including both bounds,
+    code widths, roundings, strategies, the density switch and alpha / beta: every stage
+    against the oracle for each drawn case."""
+    rng = np.random.default_rng(seed)
+    for it in range(20):
+        kind = rng.integers(0, 4)
+        if kind == 0:
+            M, N, K = (int(x) for x in rng.integers(1, 500, size=3))
+        elif kind == 1:
+            M, N, K = (int(x) * 64 for x in rng.integers(1, 9, size=3))
+        elif kind == 2:
+            M, N, K = int(rng.integers(1, 60)) * 8, int(rng.integers(1, 60)) * 4, int(rng.integers(1, 40)) * 16
+        else:
+            M, N, K = int(rng.integers(1, 8)), int(rng.integers(200, 900)), int(rng.integers(1, 1200))
+            if rng.random() < 0.5:
+                M, N = N, M
+        A = (rng.standard_normal((M, K)) * np.exp(rng.standard_normal((M, 1)))).astype(F32)
+        B = (rng.standard_normal((K, N)) * np.exp(rng.standard_normal((1, N)))).astype(F32)
+        if rng.random() < 0.3:
+            A[rng.random((M, K)) < 0.02] *= 40
+        if rng.random() < 0.3:
+            B[:, rng.integers(0, N)] = 0
+        drow, dcol = o.abs_means(o.quantized_product(A, B).D_F)
+        da, db = (float(rng.choice([0.0, 0.01, 0.05, 0.3, 1.0])) for _ in range(2))
+        ta = wl.theta_for_density(A, drow, "row", da) if (drow > 0).all() else 0.5
+        tb = wl.theta_for_density(B, dcol, "col", db) if (dcol > 0).all() else 0.5
+        bits = int(rng.choice([8, 8, 8, 4, 6]))
+        rnd = int(rng.integers(0, 2))
+        strategy = int(rng.integers(0, 3))
+        s = float(rng.choice([2.0, 2.0, 0.2, 0.0]))
+        alpha, beta = (1.0, 0.0) if rng.random() < 0.5 else (float(rng.normal()), float(rng.normal()))
+        Cin = rng.standard_normal((M, N)).astype(F32) if beta != 0.0 else None
+        try:
+            check_against_oracle(srq, b, A, B, ta, tb, bits=bits, rnd=rnd, strategy=strategy, s=s,
+                                 alpha=alpha, beta=beta, C_in=Cin)
+        except AssertionError as e:
+            raise AssertionError("case %d of seed %d: M=%d N=%d K=%d densities %.2f/%.2f bits=%d rounding=%d "
+                                 "strategy=%d s=%.1f alpha=%.3f beta=%.3f: %s"
+                                 % (it, seed, M, N, K, da, db, bits, rnd, strategy, s, alpha, beta, e)) from e
