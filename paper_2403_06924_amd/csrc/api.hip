@@ -40,6 +40,7 @@ struct Plan {
   int8_t *A_int, *B_int, *RA_int, *RB_int, *RA_em, *RB_em, *Ad, *Bd;
   float *s_a, *lam_a, *s_ra, *lam_ra, *drow, *t_a;
   float *s_b, *lam_b, *s_rb, *lam_rb, *dcol, *t_b;
+  uint32_t *amax_b, *ramax_b;   // column maxima of B and of its residual as bit patterns
   double *row_part, *col_part;
   int32_t *cnt_a, *tot_a, *a_ptr, *cnt_b, *tot_b, *b_ptr;
   int64_t* nnz;   // [2]
@@ -68,6 +69,7 @@ size_t plan_fixed(char* base, int64_t M, int64_t N, int64_t K, Plan* p) {
   p->lam_ra = c.take<float>(M); p->drow = c.take<float>(M); p->t_a = c.take<float>(M);
   p->s_b = c.take<float>(N); p->lam_b = c.take<float>(N); p->s_rb = c.take<float>(N);
   p->lam_rb = c.take<float>(N); p->dcol = c.take<float>(N); p->t_b = c.take<float>(N);
+  p->amax_b = c.take<uint32_t>(N); p->ramax_b = c.take<uint32_t>(N);
   p->row_part = c.take<double>((size_t)tiles(N, gemm_tile_n()) * M);
   p->col_part = c.take<double>((size_t)tiles(M, gemm_tile_m()) * N);
   int64_t chk = select_chunks(K);
@@ -542,15 +544,15 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     if (comp) SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_ra), p.lam_ra, M, qmax, st));
   }
   // operand B: vectors are the columns of a row-major matrix; codes are stored transposed
-  SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_b), N, 0, st));
-  if (comp) SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_rb), N, 0, st));
   if (fastB) {
-    SRQ_HIP(h, launch_cols_amax(B, K, N, ldb, reinterpret_cast<uint32_t*>(p.s_b), st));
-    SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_b), p.lam_b, N, qmax, st));
-    SRQ_HIP(h, launch_cols_codes(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.B_int, K, nullptr, 0,
-                                 comp ? reinterpret_cast<uint32_t*>(p.s_rb) : nullptr, st));
+    // one launch clears the two vectors of maxima and the per-column counts of the selection;
+    // the code and residual passes derive the scales from the maxima themselves
+    SRQ_HIP(h, launch_fill3_u32(p.amax_b, N, comp ? p.ramax_b : nullptr, N,
+                                (comp && term_b) ? reinterpret_cast<uint32_t*>(p.tot_b) : nullptr, N, st));
+    SRQ_HIP(h, launch_cols_amax(B, K, N, ldb, p.amax_b, st));
+    SRQ_HIP(h, launch_cols_codes_from_amax(B, K, N, ldb, qmax, trunc, p.amax_b, p.s_b, p.lam_b, p.B_int, K,
+                                           comp ? p.ramax_b : nullptr, st));
     if (comp) {
-      SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_rb), p.lam_rb, N, qmax, st));
       // the K-contiguous residual codes feed the matrix-core paths; the k-major copy is only
       // written now if the caller has fixed the vector-ALU path for term 1
       // (or, with SRQ_STRATEGY_AUTO, if the previous call on this handle ended up there: repeated
@@ -559,12 +561,15 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       const bool want_em = term_a && dense_fallback_density > 1.f &&
                            (strategy == SRQ_STRATEGY_CSR_VALU ||
                             (strategy == SRQ_STRATEGY_AUTO && h->last_path_a == SRQ_STRATEGY_CSR_VALU));
-      SRQ_HIP(h, launch_cols_resid(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.lam_rb,
-                                   want_em ? nullptr : p.RB_int, K, want_em ? p.RB_em : nullptr, N, st));
+      SRQ_HIP(h, launch_cols_resid_from_amax(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.ramax_b, p.s_rb,
+                                             p.lam_rb, want_em ? nullptr : p.RB_int, K,
+                                             want_em ? p.RB_em : nullptr, N, st));
       rb_vm_done = !want_em;
       rb_em_done = want_em;
     }
   } else {
+    SRQ_HIP(h, launch_fill3_u32(reinterpret_cast<uint32_t*>(p.s_b), N,
+                                comp ? reinterpret_cast<uint32_t*>(p.s_rb) : nullptr, N, nullptr, 0, st));
     SRQ_HIP(h, launch_amax(B, K, N, ldb, SRQ_AXIS_COL, reinterpret_cast<uint32_t*>(p.s_b), st));
     if (global_scale) SRQ_HIP(h, launch_broadcast_max(reinterpret_cast<uint32_t*>(p.s_b), N, st));
     SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_b), p.lam_b, N, qmax, st));
@@ -605,8 +610,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     if (term_a) SRQ_HIP(h, launch_rows_mask(A, M, K, lda, p.t_a, p.mask_a, p.tot_a, st));
     if (term_b) {
       if (fastB) {
-        SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.tot_b), N, 0, st));
-        SRQ_HIP(h, launch_cols_mask(B, K, N, ldb, p.t_b, p.mask_b, p.tot_b, st));
+        SRQ_HIP(h, launch_cols_mask(B, K, N, ldb, p.t_b, p.mask_b, p.tot_b, st));   // tot_b cleared in the quantize stage
       } else {
         SRQ_HIP(h, launch_select_count(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.cnt_b, st));
         SRQ_HIP(h, launch_select_scan(p.cnt_b, N, chk, p.tot_b, p.b_ptr, p.nnz + 1, st));

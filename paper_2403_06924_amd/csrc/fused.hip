@@ -102,6 +102,9 @@ template <int MODE>
 __global__ __launch_bounds__(256) void cols_pass_kernel(
     const float* __restrict__ X, int64_t rows, int64_t cols, int64_t ldx, float qmax, int trunc,
     const float* __restrict__ scale, const float* __restrict__ lambda, const float* __restrict__ rlambda,
+    // when given, the scales are derived here from the maxima of an earlier pass (their bit
+    // patterns) and the first row of blocks writes them out: no separate kernel in between
+    const uint32_t* __restrict__ amax_in, float* __restrict__ scale_out, float* __restrict__ lambda_out,
     const float* __restrict__ thresh, uint32_t* __restrict__ amax_bits,   // amax or residual amax (bits)
     int8_t* __restrict__ Qvm, int64_t ldvm,      // transposed output [col][row], may be null
     int8_t* __restrict__ Qem, int64_t ldem,      // straight output [row][col], may be null
@@ -166,13 +169,42 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
     return;
   }
   // codes / residual codes
-  float4 l4 = colok ? *reinterpret_cast<const float4*>(lambda + col0) : make_float4(0.f, 0.f, 0.f, 0.f);
-  float4 s4 = colok ? *reinterpret_cast<const float4*>(scale + col0) : make_float4(0.f, 0.f, 0.f, 0.f);
-  const float lam[4] = {l4.x, l4.y, l4.z, l4.w}, sc[4] = {s4.x, s4.y, s4.z, s4.w};
-  float rlam[4] = {0.f, 0.f, 0.f, 0.f};
+  float lam[4] = {0.f, 0.f, 0.f, 0.f}, sc[4] = {0.f, 0.f, 0.f, 0.f}, rlam[4] = {0.f, 0.f, 0.f, 0.f};
+  const bool writer = blockIdx.y == 0 && rb == 0 && colok;
+  if (MODE == kColsCodes && amax_in) {
+    if (colok) {
+      const uint4 a4 = *reinterpret_cast<const uint4*>(amax_in + col0);
+      const float am[4] = {__uint_as_float(a4.x), __uint_as_float(a4.y), __uint_as_float(a4.z), __uint_as_float(a4.w)};
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (am[c] > 0.f) { lam[c] = qmax / am[c]; sc[c] = am[c] / qmax; }
+    }
+    if (writer) {
+      *reinterpret_cast<float4*>(scale_out + col0) = make_float4(sc[0], sc[1], sc[2], sc[3]);
+      *reinterpret_cast<float4*>(lambda_out + col0) = make_float4(lam[0], lam[1], lam[2], lam[3]);
+    }
+  } else if (colok) {
+    float4 l4 = *reinterpret_cast<const float4*>(lambda + col0);
+    float4 s4 = *reinterpret_cast<const float4*>(scale + col0);
+    lam[0] = l4.x; lam[1] = l4.y; lam[2] = l4.z; lam[3] = l4.w;
+    sc[0] = s4.x; sc[1] = s4.y; sc[2] = s4.z; sc[3] = s4.w;
+  }
   if (MODE == kColsResid && colok) {
-    float4 r4 = *reinterpret_cast<const float4*>(rlambda + col0);
-    rlam[0] = r4.x; rlam[1] = r4.y; rlam[2] = r4.z; rlam[3] = r4.w;
+    if (amax_in) {
+      const uint4 a4 = *reinterpret_cast<const uint4*>(amax_in + col0);
+      const float am[4] = {__uint_as_float(a4.x), __uint_as_float(a4.y), __uint_as_float(a4.z), __uint_as_float(a4.w)};
+      float rs[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (am[c] > 0.f) { rlam[c] = qmax / am[c]; rs[c] = am[c] / qmax; }
+      if (writer) {
+        *reinterpret_cast<float4*>(scale_out + col0) = make_float4(rs[0], rs[1], rs[2], rs[3]);
+        *reinterpret_cast<float4*>(lambda_out + col0) = make_float4(rlam[0], rlam[1], rlam[2], rlam[3]);
+      }
+    } else {
+      float4 r4 = *reinterpret_cast<const float4*>(rlambda + col0);
+      rlam[0] = r4.x; rlam[1] = r4.y; rlam[2] = r4.z; rlam[3] = r4.w;
+    }
   }
   float rm[4] = {0.f, 0.f, 0.f, 0.f};
   unsigned packed[4][4];                            // [column][word]: 16 codes of one column
@@ -445,8 +477,8 @@ hipError_t launch_cols_amax(const float* X, int64_t rows, int64_t cols, int64_t 
                             hipStream_t st) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsAmax>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
-                     0.f, 0, nullptr, nullptr, nullptr, nullptr, amax_bits, nullptr, 0, nullptr, 0, nullptr, 0,
-                     nullptr);
+                     0.f, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, amax_bits, nullptr, 0,
+                     nullptr, 0, nullptr, 0, nullptr);
   return hipGetLastError();
 }
 
@@ -455,8 +487,31 @@ hipError_t launch_cols_codes(const float* X, int64_t rows, int64_t cols, int64_t
                              int64_t ldem, uint32_t* ramax_bits, hipStream_t st) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsCodes>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
-                     (float)qmax, trunc, scale, lambda, nullptr, nullptr, ramax_bits, Qvm, ldvm, Qem, ldem,
-                     nullptr, 0, nullptr);
+                     (float)qmax, trunc, scale, lambda, nullptr, nullptr, nullptr, nullptr, nullptr, ramax_bits,
+                     Qvm, ldvm, Qem, ldem, nullptr, 0, nullptr);
+  return hipGetLastError();
+}
+
+// the same pass with the scales derived in the kernel from the column maxima of launch_cols_amax
+hipError_t launch_cols_codes_from_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax,
+                                       int trunc, const uint32_t* amax_bits, float* scale, float* lambda,
+                                       int8_t* Qvm, int64_t ldvm, uint32_t* ramax_bits, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  hipLaunchKernelGGL(cols_pass_kernel<kColsCodes>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+                     (float)qmax, trunc, nullptr, nullptr, nullptr, amax_bits, scale, lambda, nullptr,
+                     ramax_bits, Qvm, ldvm, nullptr, 0, nullptr, 0, nullptr);
+  return hipGetLastError();
+}
+
+// residual codes with the residual scales derived in the kernel from the maxima the codes pass left
+hipError_t launch_cols_resid_from_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax,
+                                       int trunc, const float* scale, const float* lambda,
+                                       const uint32_t* ramax_bits, float* rscale, float* rlambda, int8_t* Rvm,
+                                       int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  hipLaunchKernelGGL(cols_pass_kernel<kColsResid>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+                     (float)qmax, trunc, scale, lambda, nullptr, ramax_bits, rscale, rlambda, nullptr, nullptr,
+                     Rvm, ldvm, Rem, ldem, nullptr, 0, nullptr);
   return hipGetLastError();
 }
 
@@ -465,8 +520,8 @@ hipError_t launch_cols_resid(const float* X, int64_t rows, int64_t cols, int64_t
                              int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st) {
   if (rows <= 0 || cols <= 0 || (!Rvm && !Rem)) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsResid>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
-                     (float)qmax, trunc, scale, lambda, rlambda, nullptr, nullptr, Rvm, ldvm, Rem, ldem, nullptr,
-                     0, nullptr);
+                     (float)qmax, trunc, scale, lambda, rlambda, nullptr, nullptr, nullptr, nullptr, nullptr, Rvm,
+                     ldvm, Rem, ldem, nullptr, 0, nullptr);
   return hipGetLastError();
 }
 
@@ -475,8 +530,8 @@ hipError_t launch_cols_mask(const float* X, int64_t rows, int64_t cols, int64_t 
                             uint64_t* mask, int32_t* counts, hipStream_t st) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsMask>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
-                     0.f, 0, nullptr, nullptr, nullptr, thresh, nullptr, nullptr, 0, nullptr, 0,
-                     reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts);
+                     0.f, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, thresh, nullptr, nullptr, 0,
+                     nullptr, 0, reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts);
   return hipGetLastError();
 }
 

@@ -243,6 +243,25 @@ hipError_t launch_scales(uint32_t* amax_bits_then_scale, float* lambda, int64_t 
   return hipGetLastError();
 }
 
+__global__ void fill3_u32_kernel(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, uint32_t* c, int64_t nc) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < na) a[i] = 0;
+  if (i < nb) b[i] = 0;
+  if (i < nc) c[i] = 0;
+}
+
+hipError_t launch_fill3_u32(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, uint32_t* c, int64_t nc,
+                            hipStream_t st) {
+  if (!a) na = 0;
+  if (!b) nb = 0;
+  if (!c) nc = 0;
+  int64_t n = na > nb ? na : nb;
+  n = n > nc ? n : nc;
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill3_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a, na, b, nb, c, nc);
+  return hipGetLastError();
+}
+
 hipError_t launch_broadcast_max(uint32_t* bits, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(broadcast_max_kernel, dim3(1), dim3(1024), 0, st, bits, n);

@@ -97,6 +97,16 @@ hipError_t launch_cols_amax(const float* X, int64_t rows, int64_t cols, int64_t 
 hipError_t launch_cols_codes(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                              const float* scale, const float* lambda, int8_t* Qvm, int64_t ldvm, int8_t* Qem,
                              int64_t ldem, uint32_t* ramax_bits, hipStream_t st);
+hipError_t launch_cols_codes_from_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax,
+                                       int trunc, const uint32_t* amax_bits, float* scale, float* lambda,
+                                       int8_t* Qvm, int64_t ldvm, uint32_t* ramax_bits, hipStream_t st);
+hipError_t launch_cols_resid_from_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax,
+                                       int trunc, const float* scale, const float* lambda,
+                                       const uint32_t* ramax_bits, float* rscale, float* rlambda, int8_t* Rvm,
+                                       int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st);
+// zero-fills up to three arrays of 32-bit words in one launch (null pointers are skipped)
+hipError_t launch_fill3_u32(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, uint32_t* c, int64_t nc,
+                            hipStream_t st);
 hipError_t launch_cols_resid(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                              const float* scale, const float* lambda, const float* rlambda, int8_t* Rvm,
                              int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st);
