@@ -93,9 +93,11 @@ typedef struct srq_debug_t {
 
 /* Device pointers INTO THE WORKSPACE to the intermediates of the last
  * srq_compensated_gemm call on this handle (valid until the next call or until the
- * workspace is replaced).  Code matrices: A-side M x K vector-major (ld = K); B-side
- * N x K vector-major (ld = K).  Element-major residual codes: RB_em is K x N (ld = N),
- * RA_em is K x M (ld = M); they are only filled when a term ran as CSR_VALU. */
+ * workspace is replaced).  Code matrices: A-side M x K vector-major, B-side N x K
+ * vector-major, both with leading dimension ld_codes = K rounded up to a multiple of 128
+ * (the columns past K hold zeros, so that every row starts on a 128-byte boundary whatever K
+ * is).  Element-major residual codes: RB_em is K x N (ld = N), RA_em is K x M (ld = M); they
+ * are only filled when a term ran as CSR_VALU. */
 typedef struct srq_intermediates_t {
   const int8_t *A_int, *B_int, *RA_int, *RB_int, *RA_em, *RB_em;
   const float *s_a, *lam_a, *s_ra, *s_b, *lam_b, *s_rb;   /* [M] resp. [N]                 */
@@ -103,6 +105,7 @@ typedef struct srq_intermediates_t {
   const int32_t *a_ptr, *a_idx; const int8_t* a_val;      /* CSR of A'_int                  */
   const int32_t *b_ptr, *b_idx; const int8_t* b_val;      /* CSC of B'_int                  */
   int64_t capacity_a, capacity_b;                         /* entries that fit idx/val       */
+  int64_t ld_codes;                                       /* see above                      */
 } srq_intermediates_t;
 
 /* ---- lifecycle -------------------------------------------------------------------- */

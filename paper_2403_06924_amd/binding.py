@@ -45,7 +45,7 @@ class Intermediates(C.Structure):
         "s_a", "lam_a", "s_ra", "s_b", "lam_b", "s_rb",
         "drow", "dcol", "t_a", "t_b",
         "a_ptr", "a_idx", "a_val", "b_ptr", "b_idx", "b_val")] + [
-        ("capacity_a", C.c_int64), ("capacity_b", C.c_int64)]
+        ("capacity_a", C.c_int64), ("capacity_b", C.c_int64), ("ld_codes", C.c_int64)]
 
 
 class SrqError(RuntimeError):
@@ -296,12 +296,14 @@ class Srq:
         self._ret(self.lib.srq_get_intermediates(self.h, C.byref(im)), "srq_get_intermediates")
         out = {}
 
-        def mat(name, r, c):
-            v = self._view(getattr(im, name), r * c, torch.int8)
-            out[name] = None if v is None else v.view(r, c)
+        def mat(name, r, c, ld):
+            v = self._view(getattr(im, name), r * ld, torch.int8)
+            out[name] = None if v is None else v.view(r, ld)[:, :c]
 
-        mat("A_int", M, K); mat("B_int", N, K); mat("RA_int", M, K); mat("RB_int", N, K)
-        mat("RA_em", K, M); mat("RB_em", K, N)
+        ldc = int(im.ld_codes) if im.ld_codes else K
+        mat("A_int", M, K, ldc); mat("B_int", N, K, ldc); mat("RA_int", M, K, ldc); mat("RB_int", N, K, ldc)
+        mat("RA_em", K, M, M); mat("RB_em", K, N, N)
+        out["ld_codes"] = ldc
         for name, n in (("s_a", M), ("lam_a", M), ("s_ra", M), ("drow", M), ("t_a", M),
                         ("s_b", N), ("lam_b", N), ("s_rb", N), ("dcol", N), ("t_b", N)):
             out[name] = self._view(getattr(im, name), n, torch.float32)

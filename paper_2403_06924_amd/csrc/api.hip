@@ -53,16 +53,22 @@ struct Plan {
 
 int64_t tiles(int64_t n, int t) { return (n + t - 1) / t; }
 
+// Leading dimension of the K-contiguous code matrices in the workspace: K rounded up to a
+// multiple of 128 with zeros in the padding, so that every row is 128-byte aligned and the
+// matrix-core kernels take their aligned, full-K-tile paths whatever K is (zero codes add nothing).
+int64_t code_ld(int64_t K) { return (K + 127) / 128 * 128; }
+
 // Lays the fixed-size regions out; returns the bytes they take.  base may be null (sizing).
 size_t plan_fixed(char* base, int64_t M, int64_t N, int64_t K, Plan* p) {
   Carver c{base, 0};
-  size_t mk = (size_t)M * K, nk = (size_t)N * K;
+  const int64_t Kc = code_ld(K);
+  size_t mk = (size_t)M * Kc, nk = (size_t)N * Kc;
   p->A_int = c.take<int8_t>(mk);
   p->B_int = c.take<int8_t>(nk);
   p->RA_int = c.take<int8_t>(mk);
   p->RB_int = c.take<int8_t>(nk);
-  p->RA_em = c.take<int8_t>(mk);
-  p->RB_em = c.take<int8_t>(nk);
+  p->RA_em = c.take<int8_t>((size_t)M * K);
+  p->RB_em = c.take<int8_t>((size_t)N * K);
   p->Ad = c.take<int8_t>(mk);
   p->Bd = c.take<int8_t>(nk);
   p->s_a = c.take<float>(M); p->lam_a = c.take<float>(M); p->s_ra = c.take<float>(M);
@@ -512,25 +518,34 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   if (comp) plan_compressed(base, h->ws_bytes, M, N, K, &p);
   const int trunc = round == SRQ_ROUND_TRUNC;
   const bool scale_needed = alpha != 1.f || beta != 0.f;
+  const int64_t Kc = code_ld(K);                 // leading dimension of the K-contiguous code matrices
 
   srq_intermediates_t& im = h->last;
   memset(&im, 0, sizeof(im));
+  im.ld_codes = Kc;
   im.A_int = p.A_int; im.B_int = p.B_int; im.s_a = p.s_a; im.lam_a = p.lam_a; im.s_b = p.s_b; im.lam_b = p.lam_b;
 
   h->prof_used = 0;
   // the one-pass kernels derive each vector's scale from the data they hold; a matrix-wide
   // scale needs all maxima first and takes the staged kernels
   const bool global_scale = h->scale_mode == SRQ_SCALE_GLOBAL;
-  const bool fastA = K > 0 && !global_scale && rows_fused_ok(A, K, lda, p.A_int, K, p.RA_int, K);
+  const bool fastA = K > 0 && !global_scale && rows_fused_ok(A, K, lda, p.A_int, Kc, p.RA_int, Kc);
   const bool fastB = K > 0 && !global_scale && cols_pass_ok(B, N, ldb);
   bool ra_vm_done = false, rb_vm_done = false, rb_em_done = false;
   // lines 1: Quant.  amax per vector -> scale, lambda -> codes (and max |residual| per vector)
   {
   StageTimer tm(h, st, SRQ_STAGE_QUANTIZE);
+  if (Kc != K) {
+    // the padding columns of every matrix a product may read (nothing else ever writes them)
+    int8_t* mats[6] = {p.A_int, p.B_int, comp ? p.RA_int : nullptr, comp ? p.RB_int : nullptr,
+                       comp ? p.Ad : nullptr, comp ? p.Bd : nullptr};
+    const int64_t nrows[6] = {M, N, M, N, M, N};
+    SRQ_HIP(h, launch_zero_pad(mats, nrows, 6, K, Kc, st));
+  }
   // operand A: vectors are contiguous rows
   if (fastA) {
-    SRQ_HIP(h, launch_rows_fused(A, M, K, lda, qmax, trunc, p.A_int, K, p.s_a, p.lam_a,
-                                 comp ? p.RA_int : nullptr, K, p.s_ra, p.lam_ra, st));
+    SRQ_HIP(h, launch_rows_fused(A, M, K, lda, qmax, trunc, p.A_int, Kc, p.s_a, p.lam_a,
+                                 comp ? p.RA_int : nullptr, Kc, p.s_ra, p.lam_ra, st));
     ra_vm_done = comp;
   } else {
     SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_a), M, 0, st));
@@ -539,7 +554,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     if (global_scale) SRQ_HIP(h, launch_broadcast_max(reinterpret_cast<uint32_t*>(p.s_a), M, st));
     SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_a), p.lam_a, M, qmax, st));
     SRQ_HIP(h, launch_quantize_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, qmax, trunc,
-                                     SRQ_LAYOUT_VECTOR_MAJOR, p.A_int, K,
+                                     SRQ_LAYOUT_VECTOR_MAJOR, p.A_int, Kc,
                                      comp ? reinterpret_cast<uint32_t*>(p.s_ra) : nullptr, st));
     if (comp) SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_ra), p.lam_ra, M, qmax, st));
   }
@@ -550,7 +565,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     SRQ_HIP(h, launch_fill3_u32(p.amax_b, N, comp ? p.ramax_b : nullptr, N,
                                 (comp && term_b) ? reinterpret_cast<uint32_t*>(p.tot_b) : nullptr, N, st));
     SRQ_HIP(h, launch_cols_amax(B, K, N, ldb, p.amax_b, st));
-    SRQ_HIP(h, launch_cols_codes_from_amax(B, K, N, ldb, qmax, trunc, p.amax_b, p.s_b, p.lam_b, p.B_int, K,
+    SRQ_HIP(h, launch_cols_codes_from_amax(B, K, N, ldb, qmax, trunc, p.amax_b, p.s_b, p.lam_b, p.B_int, Kc,
                                            comp ? p.ramax_b : nullptr, st));
     if (comp) {
       // the K-contiguous residual codes feed the matrix-core paths; the k-major copy is only
@@ -562,7 +577,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
                            (strategy == SRQ_STRATEGY_CSR_VALU ||
                             (strategy == SRQ_STRATEGY_AUTO && h->last_path_a == SRQ_STRATEGY_CSR_VALU));
       SRQ_HIP(h, launch_cols_resid_from_amax(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.ramax_b, p.s_rb,
-                                             p.lam_rb, want_em ? nullptr : p.RB_int, K,
+                                             p.lam_rb, want_em ? nullptr : p.RB_int, Kc,
                                              want_em ? p.RB_em : nullptr, N, st));
       rb_vm_done = !want_em;
       rb_em_done = want_em;
@@ -574,7 +589,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     if (global_scale) SRQ_HIP(h, launch_broadcast_max(reinterpret_cast<uint32_t*>(p.s_b), N, st));
     SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_b), p.lam_b, N, qmax, st));
     SRQ_HIP(h, launch_quantize_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, qmax, trunc,
-                                     SRQ_LAYOUT_VECTOR_MAJOR, p.B_int, K,
+                                     SRQ_LAYOUT_VECTOR_MAJOR, p.B_int, Kc,
                                      comp ? reinterpret_cast<uint32_t*>(p.s_rb) : nullptr, st));
     if (comp) SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_rb), p.lam_rb, N, qmax, st));
   }
@@ -595,7 +610,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   ep.final_scale = !comp && scale_needed;
   {
     StageTimer tm(h, st, SRQ_STAGE_GEMM);
-    SRQ_HIP(h, launch_gemm_i8(M, N, K, p.A_int, K, p.B_int, K, ep, st));
+    SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.A_int, Kc, p.B_int, Kc, ep, st));
   }
   int path_a = 0, path_b = 0;
   if (comp) {
@@ -647,18 +662,18 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // compaction to CSR of A' / CSC of B'; a term that will run on the matrix cores also gets
     // its operand expanded to zero-filled dense codes in the same pass
     if (term_a) {
-      SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, K, p.a_ptr, p.a_idx, p.a_val, p.cap_a,
-                                     path_a == 2 ? p.Ad : nullptr, K, st));
+      SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, Kc, p.a_ptr, p.a_idx, p.a_val, p.cap_a,
+                                     path_a == 2 ? p.Ad : nullptr, Kc, st));
       im.a_ptr = p.a_ptr; im.a_idx = p.a_idx; im.a_val = p.a_val; im.capacity_a = p.cap_a;
     }
     if (term_b) {
       if (fastB) {
-        SRQ_HIP(h, launch_scatter_mask(p.mask_b, N, K, p.B_int, K, p.b_ptr, p.b_idx, p.b_val, p.cap_b,
-                                       path_b == 2 ? p.Bd : nullptr, K, st));
+        SRQ_HIP(h, launch_scatter_mask(p.mask_b, N, K, p.B_int, Kc, p.b_ptr, p.b_idx, p.b_val, p.cap_b,
+                                       path_b == 2 ? p.Bd : nullptr, Kc, st));
       } else {
         SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
                                          p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));
-        if (path_b == 2) SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, K, st));
+        if (path_b == 2) SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, Kc, st));
       }
       im.b_ptr = p.b_ptr; im.b_idx = p.b_idx; im.b_val = p.b_val; im.capacity_b = p.cap_b;
     }
@@ -673,14 +688,14 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     const bool need_rb_em = rb_em && !rb_em_done;
     if (need_ra_vm || ra_em)
       SRQ_HIP(h, launch_residual_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, p.lam_ra, qmax, trunc,
-                                       need_ra_vm ? p.RA_int : nullptr, K, ra_em ? p.RA_em : nullptr, M, st));
+                                       need_ra_vm ? p.RA_int : nullptr, Kc, ra_em ? p.RA_em : nullptr, M, st));
     if (need_rb_vm || need_rb_em) {
       if (fastB)
         SRQ_HIP(h, launch_cols_resid(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.lam_rb,
-                                     need_rb_vm ? p.RB_int : nullptr, K, need_rb_em ? p.RB_em : nullptr, N, st));
+                                     need_rb_vm ? p.RB_int : nullptr, Kc, need_rb_em ? p.RB_em : nullptr, N, st));
       else
         SRQ_HIP(h, launch_residual_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, p.lam_rb, qmax, trunc,
-                                         need_rb_vm ? p.RB_int : nullptr, K, need_rb_em ? p.RB_em : nullptr, N,
+                                         need_rb_vm ? p.RB_int : nullptr, Kc, need_rb_em ? p.RB_em : nullptr, N,
                                          st));
     }
     }
@@ -700,10 +715,10 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.a_ptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, e1, st));
     } else if (path_a == 2) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
-      SRQ_HIP(h, launch_gemm_i8(M, N, K, p.Ad, K, p.RB_int, K, e1, st));
+      SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, e1, st));
     } else if (path_a == 3) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
-      SRQ_HIP(h, launch_gemm_i8(M, N, K, p.A_int, K, p.RB_int, K, e1, st));
+      SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.A_int, Kc, p.RB_int, Kc, e1, st));
     }
     GemmEpilogue e2 = e1;
     e2.s_row = p.s_ra; e2.s_col = p.s_b;
@@ -714,10 +729,10 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.b_ptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, e2, st));
     } else if (path_b == 2) {
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
-      SRQ_HIP(h, launch_gemm_i8(M, N, K, p.RA_int, K, p.Bd, K, e2, st));
+      SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.RA_int, Kc, p.Bd, Kc, e2, st));
     } else if (path_b == 3) {
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
-      SRQ_HIP(h, launch_gemm_i8(M, N, K, p.RA_int, K, p.B_int, K, e2, st));
+      SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.RA_int, Kc, p.B_int, Kc, e2, st));
     }
     if (scale_needed && path_a == 0 && path_b == 0) {
       GemmEpilogue e3 = ep;

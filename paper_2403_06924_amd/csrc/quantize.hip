@@ -250,6 +250,35 @@ __global__ void fill3_u32_kernel(uint32_t* a, int64_t na, uint32_t* b, int64_t n
   if (i < nc) c[i] = 0;
 }
 
+struct PadArgs { int8_t* m[6]; int64_t rows[6]; };
+
+// one thread per (matrix, row, padding byte)
+__global__ void zero_pad_kernel(PadArgs a, int n, int64_t cols, int64_t ld) {
+  const int64_t pad = ld - cols;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int which = blockIdx.y;
+  if (which >= n || !a.m[which]) return;
+  const int64_t r = i / pad, c = i - r * pad;
+  if (r < a.rows[which]) a.m[which][r * ld + cols + c] = 0;
+}
+
+hipError_t launch_zero_pad(int8_t* const* mats, const int64_t* rows, int n, int64_t cols, int64_t ld,
+                           hipStream_t st) {
+  if (ld <= cols || n <= 0) return hipSuccess;
+  PadArgs a;
+  int64_t most = 0;
+  for (int i = 0; i < 6; ++i) {
+    a.m[i] = i < n ? mats[i] : nullptr;
+    a.rows[i] = i < n ? rows[i] : 0;
+    if (a.m[i] && a.rows[i] > most) most = a.rows[i];
+  }
+  if (most <= 0) return hipSuccess;
+  const int64_t work = most * (ld - cols);
+  hipLaunchKernelGGL(zero_pad_kernel, dim3((unsigned)((work + 255) / 256), (unsigned)n), dim3(256), 0, st, a, n,
+                     cols, ld);
+  return hipGetLastError();
+}
+
 hipError_t launch_fill3_u32(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, uint32_t* c, int64_t nc,
                             hipStream_t st) {
   if (!a) na = 0;

@@ -104,6 +104,9 @@ hipError_t launch_cols_resid_from_amax(const float* X, int64_t rows, int64_t col
                                        int trunc, const float* scale, const float* lambda,
                                        const uint32_t* ramax_bits, float* rscale, float* rlambda, int8_t* Rvm,
                                        int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st);
+// zeroes columns [cols, ld) of up to six row-major byte matrices of `rows[i]` rows each (null: skipped)
+hipError_t launch_zero_pad(int8_t* const* mats, const int64_t* rows, int n, int64_t cols, int64_t ld,
+                           hipStream_t st);
 // zero-fills up to three arrays of 32-bit words in one launch (null pointers are skipped)
 hipError_t launch_fill3_u32(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, uint32_t* c, int64_t nc,
                             hipStream_t st);
