@@ -195,7 +195,10 @@ srq_status_t srq_build_sparse_residual(srq_handle_t handle, const float* X, int6
 /* D_int[i,j] = sum_k Qa[i*lda+k] * Qb[j*ldb+k]  (both operands vector-major, K contiguous);
  * D_F[i,j] = fl(fl(float(D_int)) * fl(sa[i]*sb[j])).  D_int (ld = ldd) may be NULL.
  * drow[M], dcol[N] receive the means of |D_F| over each row / column (Sec. 3.1.1), summed
- * in double in a fixed order; both may be NULL. */
+ * in double in a fixed order; both may be NULL.
+ * Any shape and alignment is accepted; the fast kernels need 16-byte aligned Qa, Qb, lda and ldb
+ * multiples of 16 and K a multiple of 64 (pad K with zero codes to get there: they add nothing),
+ * and the persistent one in addition M and N multiples of 256 with at least 256 tiles. */
 srq_status_t srq_gemm_i8(srq_handle_t handle, int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
                          const float* sa, const int8_t* Qb, int64_t ldb, const float* sb, float* D_F,
                          int32_t* D_int, int64_t ldd, float* drow, float* dcol, void* stream);
