@@ -218,7 +218,8 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
 #pragma unroll
         for (int v = 0; v < 16; ++v)
 #pragma unroll
-          for (int b = 0; b < TN; ++b) x[b][v] = cband[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32];
+          for (int b = 0; b < TN; ++b)
+            x[b][v] = __builtin_nontemporal_load(&cband[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32]);
       }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
             out = ep.alpha * out;
             if (ep.beta != 0.f) out = out + ep.beta * ep.Cin[(m0 + rbase + ro) * ep.ldcin + n0 + cbase + b * 32];
           }
-          cband[(int64_t)ro * ep.ldc + b * 32] = out;
+          __builtin_nontemporal_store(out, &cband[(int64_t)ro * ep.ldc + b * 32]);
           if (SUMS) x[b][v] = fabsf(d);
           acc[a][b][v] = 0;
         }
