@@ -87,8 +87,10 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
   for (int i = 0; i < NV4; ++i) {
     int64_t c4 = threadIdx.x + i * 256;
     if (c4 < n4)
-      rdst[c4] = pack4(quant_code(x[i].x, rlam, qmax, trunc), quant_code(x[i].y, rlam, qmax, trunc),
-                       quant_code(x[i].z, rlam, qmax, trunc), quant_code(x[i].w, rlam, qmax, trunc));
+      // (residual codes are first read two products later: kept out of the caches)
+      __builtin_nontemporal_store(pack4(quant_code(x[i].x, rlam, qmax, trunc), quant_code(x[i].y, rlam, qmax, trunc),
+                                        quant_code(x[i].z, rlam, qmax, trunc), quant_code(x[i].w, rlam, qmax, trunc)),
+                                  &rdst[c4]);
   }
   if (threadIdx.x == 0) { rscale[row] = rs; rlambda[row] = rlam; }
 }
@@ -237,7 +239,10 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
     for (int c = 0; c < 4; ++c) {
       int8_t* dst = Qvm + (col0 + c) * ldvm + row0;
       if (full) {
-        *reinterpret_cast<uint4*>(dst) = make_uint4(packed[c][0], packed[c][1], packed[c][2], packed[c][3]);
+        typedef unsigned u4v __attribute__((ext_vector_type(4)));
+        u4v pk = {packed[c][0], packed[c][1], packed[c][2], packed[c][3]};
+        if (MODE == kColsResid) __builtin_nontemporal_store(pk, reinterpret_cast<u4v*>(dst));
+        else *reinterpret_cast<u4v*>(dst) = pk;
       } else {
         for (int i = 0; i < 16; ++i)
           if (row0 + i < rows) dst[i] = (int8_t)((packed[c][i >> 2] >> (8 * (i & 3))) & 0xff);
