@@ -33,6 +33,14 @@ __device__ __forceinline__ float block_max_256(float m, float* sm) {
   return fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
 }
 
+// 16-byte load that does not displace cached data (used for the last read of an operand before
+// a product runs in between)
+__device__ __forceinline__ float4 load_streaming(const float4* p) {
+  typedef float f4v __attribute__((ext_vector_type(4)));
+  f4v t = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p));
+  return make_float4(t.x, t.y, t.z, t.w);
+}
+
 __device__ __forceinline__ unsigned pack4(int a, int b, int c, int d) {
   return (unsigned)(a & 0xff) | ((unsigned)(b & 0xff) << 8) | ((unsigned)(c & 0xff) << 16) |
          ((unsigned)(d & 0xff) << 24);
@@ -56,7 +64,7 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
 #pragma unroll
   for (int i = 0; i < NV4; ++i) {
     int64_t c4 = threadIdx.x + i * 256;
-    x[i] = c4 < n4 ? src[c4] : make_float4(0.f, 0.f, 0.f, 0.f);
+    x[i] = c4 < n4 ? load_streaming(src + c4) : make_float4(0.f, 0.f, 0.f, 0.f);
     m = fmaxf(m, fmaxf(fmaxf(fabsf(x[i].x), fabsf(x[i].y)), fmaxf(fabsf(x[i].z), fabsf(x[i].w))));
   }
   const float amax = block_max_256(m, sm);
@@ -69,7 +77,7 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
     int64_t c4 = threadIdx.x + i * 256;
     int q0 = quant_code(x[i].x, lam, qmax, trunc), q1 = quant_code(x[i].y, lam, qmax, trunc);
     int q2 = quant_code(x[i].z, lam, qmax, trunc), q3 = quant_code(x[i].w, lam, qmax, trunc);
-    if (c4 < n4) qdst[c4] = pack4(q0, q1, q2, q3);
+    if (c4 < n4) __builtin_nontemporal_store(pack4(q0, q1, q2, q3), &qdst[c4]);
     if (Rq) {
       // residual r = fl(x - fl(float(q) * s)); kept in place of x
       x[i].x = x[i].x - (float)q0 * s; x[i].y = x[i].y - (float)q1 * s;
@@ -125,8 +133,10 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     int64_t r = row0 + i;
-    v[i] = (colok && r < rows) ? *reinterpret_cast<const float4*>(X + r * ldx + col0)
-                               : make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4* src = reinterpret_cast<const float4*>(X + r * ldx + col0);
+    const bool ok = colok && r < rows;
+    if (MODE == kColsResid || MODE == kColsMask) v[i] = ok ? load_streaming(src) : make_float4(0.f, 0.f, 0.f, 0.f);
+    else v[i] = ok ? *src : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   if (MODE == kColsAmax) {
     float m[4] = {0.f, 0.f, 0.f, 0.f};
@@ -241,8 +251,7 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
       if (full) {
         typedef unsigned u4v __attribute__((ext_vector_type(4)));
         u4v pk = {packed[c][0], packed[c][1], packed[c][2], packed[c][3]};
-        if (MODE == kColsResid) __builtin_nontemporal_store(pk, reinterpret_cast<u4v*>(dst));
-        else *reinterpret_cast<u4v*>(dst) = pk;
+        __builtin_nontemporal_store(pk, reinterpret_cast<u4v*>(dst));
       } else {
         for (int i = 0; i < 16; ++i)
           if (row0 + i < rows) dst[i] = (int8_t)((packed[c][i >> 2] >> (8 * (i & 3))) & 0xff);
@@ -300,7 +309,7 @@ __global__ __launch_bounds__(256) void rows_mask_vec_kernel(const float* __restr
 #pragma unroll
   for (int i = 0; i < NV4; ++i) {
     int64_t c4 = threadIdx.x + i * 256;
-    x[i] = c4 < n4 ? src[c4] : make_float4(0.f, 0.f, 0.f, 0.f);   // |0| > t is false for every t >= 0
+    x[i] = c4 < n4 ? load_streaming(src + c4) : make_float4(0.f, 0.f, 0.f, 0.f);   // |0| > t is false for every t >= 0
   }
   uint8_t* mrow = mask + row * mask_stride;
   int total = 0;
@@ -382,7 +391,7 @@ __global__ __launch_bounds__(256) void scatter_mask_kernel(const uint64_t* __res
                               ((nib & 4u) ? 0xff0000u : 0u) | ((nib & 8u) ? 0xff000000u : 0u);
         const unsigned out = code & keep;
         if (dvec && left >= 4) {
-          *reinterpret_cast<unsigned*>(dv + e) = out;
+          __builtin_nontemporal_store(out, reinterpret_cast<unsigned*>(dv + e));
         } else {
           for (int j = 0; j < 4 && j < left; ++j) dv[e + j] = (int8_t)(out >> (8 * j));
         }
