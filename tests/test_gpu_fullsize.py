@@ -212,3 +212,35 @@ def test_persistent_gemm_uneven_tile_counts(srq, b, shape):
                         torch.from_numpy(c.idx).cuda(), torch.from_numpy(c.val).cuda(), dQb, dsa, dsb, Cd)
     ref_C = C0 + o.dequant_product(o.int_matmul(np.where(mask, Qa, 0), Qb.T), sa, sb)
     assert (host(Cd) == ref_C).all()
+
+
+@pytest.mark.parametrize("shape", [(4352, 4096, 200), (4096, 5120, 129)])
+@pytest.mark.parametrize("variant", ["mfma", "auto_sparse", "dense_branch"])
+def test_padded_inner_dimension_through_persistent_kernels(srq, b, shape, variant):
+    """K that is no multiple of 64 with M, N multiples of 256: the code matrices are padded to a
+    leading dimension of 256 with zero columns and the persistent kernels run on the padded K.
+    The timed configuration (no debug outputs), every path, element by element, with alpha."""
+    M, N, K = shape
+    rng = np.random.default_rng(M + N + K)
+    A = (rng.standard_normal((M, K)) * np.exp(rng.standard_normal((M, 1)))).astype(F32)
+    B = (rng.standard_normal((K, N)) * np.exp(rng.standard_normal((1, N)))).astype(F32)
+    strategy, s, density = {"mfma": (b.STRATEGY_CSR_MFMA, 2.0, 0.05), "auto_sparse": (b.STRATEGY_AUTO, 2.0, 0.004),
+                            "dense_branch": (b.STRATEGY_CSR_MFMA, 0.01, 0.05)}[variant]
+    drow, dcol = o.abs_means(o.quantized_product(A, B).D_F)
+    ta = wl.theta_for_density(A, drow, "row", density)
+    tb = wl.theta_for_density(B, dcol, "col", density)
+    stats = b.stats_tensor()
+    C, _, _ = srq.compensated_gemm(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), ta, tb, strategy=strategy,
+                                   dense_fallback_density=s, stats=stats, alpha=0.5)
+    torch.cuda.synchronize()
+    im = srq.intermediates(M, N, K)
+    st = b.read_stats(stats)
+    assert im["ld_codes"] == 256
+    ref = o.compensated_gemm(A, B, ta, tb, alpha=0.5, dense_fallback_density=s, thresh_a=host(im["t_a"]),
+                             thresh_b=host(im["t_b"]))
+    assert st["path_a"] == st["path_b"] == {"mfma": 2, "auto_sparse": 1, "dense_branch": 3}[variant]
+    assert (host(im["A_int"]) == ref.A_int).all() and (host(im["B_int"]) == ref.B_int.T).all()
+    assert st["nnz_a"] == ref.csr_a.nnz and st["nnz_b"] == ref.csc_b.nnz
+    assert (host(im["a_idx"]) == ref.csr_a.idx).all() and (host(im["b_val"]) == ref.csc_b.val).all()
+    assert o.error_rel(ref.C, host(C)) <= REL_TOL
+    assert (host(C) == ref.C).mean() > 0.999
