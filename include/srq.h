@@ -103,7 +103,8 @@ typedef struct srq_intermediates_t {
   const float *s_a, *lam_a, *s_ra, *s_b, *lam_b, *s_rb;   /* [M] resp. [N]                 */
   const float *drow, *dcol, *t_a, *t_b;                   /* [M] resp. [N]                 */
   const int32_t *a_ptr, *a_idx; const int8_t* a_val;      /* CSR of A'_int                  */
-  const int32_t *b_ptr, *b_idx; const int8_t* b_val;      /* CSC of B'_int                  */
+  const int32_t *b_ptr, *b_idx; const int8_t* b_val;      /* CSC of B'_int; idx and val are */
+                                                          /* NULL for a dense-branch term   */
   int64_t capacity_a, capacity_b;                         /* entries that fit idx/val       */
   int64_t ld_codes;                                       /* see above                      */
 } srq_intermediates_t;

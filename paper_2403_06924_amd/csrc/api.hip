@@ -640,10 +640,6 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       SRQ_HIP(h, hipMemcpyAsync(h->host_nnz, p.nnz, 2 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
       SRQ_HIP(h, hipStreamSynchronize(st));
       int64_t na = term_a ? h->host_nnz[0] : 0, nb = term_b ? h->host_nnz[1] : 0;
-      if (na > p.cap_a || nb > p.cap_b) {
-        if (stats_dev) SRQ_HIP(h, launch_stats(term_a ? p.nnz : nullptr, term_b ? p.nnz + 1 : nullptr, 0, 0, stats_dev, st));
-        return SRQ_STATUS_CAPACITY;
-      }
       double da = (double)na / ((double)M * (double)K), db = (double)nb / ((double)N * (double)K);
       auto pick = [&](double d, double crossover) {
         if (d >= (double)dense_fallback_density) return 3;
@@ -655,18 +651,29 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       if (term_a) path_a = pick(da, K > 8192 ? kAutoMfmaDensityALongK : kAutoMfmaDensityA);
       if (term_b) path_b = pick(db, kAutoMfmaDensityB);
       if (term_a && strategy == SRQ_STRATEGY_AUTO) h->last_path_a = path_a;
+      // an operand on the dense branch is not compacted, so only the others need room
+      if ((path_a != 3 && na > p.cap_a) || (path_b != 3 && nb > p.cap_b)) {
+        if (stats_dev) SRQ_HIP(h, launch_stats(term_a ? p.nnz : nullptr, term_b ? p.nnz + 1 : nullptr, 0, 0, stats_dev, st));
+        return SRQ_STATUS_CAPACITY;
+      }
     } else {
       if (term_a) path_a = (int)strategy;
       if (term_b) path_b = (int)strategy;
     }
     // compaction to CSR of A' / CSC of B'; a term that will run on the matrix cores also gets
     // its operand expanded to zero-filled dense codes in the same pass
+    // (the dense branch multiplies the unreduced codes: its operand is counted, not compacted)
     if (term_a) {
-      SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, Kc, p.a_ptr, p.a_idx, p.a_val, p.cap_a,
-                                     path_a == 2 ? p.Ad : nullptr, Kc, st));
-      im.a_ptr = p.a_ptr; im.a_idx = p.a_idx; im.a_val = p.a_val; im.capacity_a = p.cap_a;
+      im.a_ptr = p.a_ptr; im.capacity_a = p.cap_a;
+      if (path_a != 3) {
+        SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, Kc, p.a_ptr, p.a_idx, p.a_val, p.cap_a,
+                                       path_a == 2 ? p.Ad : nullptr, Kc, st));
+        im.a_idx = p.a_idx; im.a_val = p.a_val;
+      }
     }
-    if (term_b) {
+    if (term_b && path_b == 3) {
+      im.b_ptr = p.b_ptr; im.capacity_b = p.cap_b;
+    } else if (term_b) {
       if (fastB) {
         SRQ_HIP(h, launch_scatter_mask(p.mask_b, N, K, p.B_int, Kc, p.b_ptr, p.b_idx, p.b_val, p.cap_b,
                                        path_b == 2 ? p.Bd : nullptr, Kc, st));

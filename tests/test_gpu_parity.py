@@ -267,15 +267,17 @@ def check_against_oracle(srq, b, A, B, theta_a, theta_b, *, bits=8, rnd=0, strat
         if not np.isinf(theta_a):
             assert st["nnz_a"] == ref.csr_a.nnz
             assert (host(im["a_ptr"]) == ref.csr_a.ptr).all()
-            assert (host(im["a_idx"]) == ref.csr_a.idx).all()
-            assert (host(im["a_val"]) == ref.csr_a.val).all()
+            if st["path_a"] != 3:                                # the dense branch counts, it does not compact
+                assert (host(im["a_idx"]) == ref.csr_a.idx).all()
+                assert (host(im["a_val"]) == ref.csr_a.val).all()
             assert st["path_a"] == (3 if ref.dense_a else st["path_a"]) and st["path_a"] in (1, 2, 3)
             assert (host(dbg["DR1_int"]) == ref.DR1_int).all()
         if not np.isinf(theta_b):
             assert st["nnz_b"] == ref.csc_b.nnz
             assert (host(im["b_ptr"]) == ref.csc_b.ptr).all()
-            assert (host(im["b_idx"]) == ref.csc_b.idx).all()
-            assert (host(im["b_val"]) == ref.csc_b.val).all()
+            if st["path_b"] != 3:
+                assert (host(im["b_idx"]) == ref.csc_b.idx).all()
+                assert (host(im["b_val"]) == ref.csc_b.val).all()
             assert (host(dbg["DR2_int"]) == ref.DR2_int).all()
         for key, mat in (("RA_int", ref.RA_int), ("RB_int", ref.RB_int.T), ("RA_em", ref.RA_int.T),
                          ("RB_em", ref.RB_int)):
