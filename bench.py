@@ -185,7 +185,7 @@ def main():
         t = sum(t for t, _ in valu_ms)
         macs = sum(m for _, m in valu_ms)
         ach = 2.0 * macs / (t * 1e-3) / 1e12
-        roof = {"kernel": "spmm_valu_kernel", "bound": "alu", "achieved": ach, "peak": PEAK_VALU_INT_TOPS,
+        roof = {"kernel": "spmm_tile_kernel", "bound": "alu", "achieved": ach, "peak": PEAK_VALU_INT_TOPS,
                 "unit": "TOP/s", "frac": ach / PEAK_VALU_INT_TOPS, "traffic": None,
                 "launches_per_step": len(valu_ms), "avg_launch_ms": t / len(valu_ms)}
 
