@@ -18,12 +18,13 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // (the paper's switch between SPMM and GEMM, Algorithm 1 lines 11-15, with the ratio of the
 // two kernels' throughputs on MI355X in place of the paper's eta).  Measured at 8192^3: the
 // vector-ALU kernel takes 0.19 ms + 0.30 ms per percent of density for A' (rows of C written
-// straight), 0.25 ms + 0.36 ms per percent for B' (columns of C, through LDS); the expanded
-// operand on the matrix cores takes 0.52-0.58 ms at any density.  The same crossovers (1.3-1.5 %
+// straight), 0.15 ms + 0.37 ms per percent for B' (columns of C, through LDS); the expanded
+// operand on the matrix cores takes 0.49-0.58 ms at any density.  The same crossovers (1.3-1.5 %
 // and 0.75 %) were measured at 2048^3 and 4096^3.
 constexpr double kAutoMfmaDensityA = 0.012;
 constexpr double kAutoMfmaDensityALongK = 0.008;
-constexpr double kAutoMfmaDensityB = 0.0075;
+constexpr double kAutoMfmaDensityB = 0.009;
+constexpr double kAutoMfmaDensityBLongK = 0.0075;
 
 struct Carver {
   char* base;
@@ -649,7 +650,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       // (for K > 8192 the K x 512-byte slab of codes an XCD gathers from outgrows its L2 and the
       // vector-ALU kernel loses earlier: measured crossover 0.8 % at 16384^3)
       if (term_a) path_a = pick(da, K > 8192 ? kAutoMfmaDensityALongK : kAutoMfmaDensityA);
-      if (term_b) path_b = pick(db, kAutoMfmaDensityB);
+      if (term_b) path_b = pick(db, K > 8192 ? kAutoMfmaDensityBLongK : kAutoMfmaDensityB);
       if (term_a && strategy == SRQ_STRATEGY_AUTO) h->last_path_a = path_a;
       // an operand on the dense branch is not compacted, so only the others need room
       if ((path_a != 3 && na > p.cap_a) || (path_b != 3 && nb > p.cap_b)) {

@@ -229,8 +229,38 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
   }
   if (SIDE == 1) {
     __syncthreads();
+    const int64_t j0 = (int64_t)vb * kVecPerBlock;
+    // fast form: the 32 columns of the block exist and rows of C are 16-byte aligned, so a thread
+    // adds to four consecutive columns of one row at a time (eight threads per 128-byte segment)
+    if (cvec && j0 + kVecPerBlock <= nvec) {
+      const int q = threadIdx.x & 7;                     // which four columns
+      const float4 sc4 = *reinterpret_cast<const float4*>(ep.s_col + j0 + 4 * q);
+      const int* t0 = tile + (4 * q) * LDT;
+#pragma unroll 4
+      for (int e = threadIdx.x >> 3; e < E; e += 32) {
+        const int64_t i = (int64_t)chunk * E + e;
+        if (i >= nelem) continue;
+        const float sr = ep.s_row[i];
+        float* c = ep.C + i * ep.ldc + j0 + 4 * q;
+        float4 o = *reinterpret_cast<const float4*>(c);
+        o.x = o.x + (float)t0[e] * (sr * sc4.x);
+        o.y = o.y + (float)t0[LDT + e] * (sr * sc4.y);
+        o.z = o.z + (float)t0[2 * LDT + e] * (sr * sc4.z);
+        o.w = o.w + (float)t0[3 * LDT + e] * (sr * sc4.w);
+        if (ep.final_scale) {
+          o.x = ep.alpha * o.x; o.y = ep.alpha * o.y; o.z = ep.alpha * o.z; o.w = ep.alpha * o.w;
+          if (ep.beta != 0.f) {
+            const float4 ci = *reinterpret_cast<const float4*>(ep.Cin + i * ep.ldcin + j0 + 4 * q);
+            o.x = o.x + ep.beta * ci.x; o.y = o.y + ep.beta * ci.y;
+            o.z = o.z + ep.beta * ci.z; o.w = o.w + ep.beta * ci.w;
+          }
+        }
+        *reinterpret_cast<float4*>(c) = o;
+      }
+      return;
+    }
     const int j = threadIdx.x & 31;                      // column of C inside the block of 32
-    const int64_t jj = (int64_t)vb * kVecPerBlock + j;
+    const int64_t jj = j0 + j;
     const float sc = jj < nvec ? ep.s_col[jj] : 0.f;
 #pragma unroll 8
     for (int e = threadIdx.x >> 5; e < E; e += 8) {
@@ -258,7 +288,7 @@ hipError_t launch_tile(int64_t nvec, int64_t nelem, const int32_t* ptr, const in
   const int64_t nch = (nelem + E - 1) / E;
   const int64_t blocks = (nch + 7) / 8 * 8 * nvb;
   // side 0 adds to C with 16-byte accesses when every row segment of a lane is aligned
-  const bool cvec = SIDE == 0 && !ep.D_int && (reinterpret_cast<uintptr_t>(ep.C) & 15) == 0 && ep.ldc % 4 == 0 &&
+  const bool cvec = !ep.D_int && (reinterpret_cast<uintptr_t>(ep.C) & 15) == 0 && ep.ldc % 4 == 0 &&
                     (reinterpret_cast<uintptr_t>(ep.s_col) & 15) == 0 &&
                     (!ep.Cin || ((reinterpret_cast<uintptr_t>(ep.Cin) & 15) == 0 && ep.ldcin % 4 == 0));
   const size_t lds = SIDE == 1 ? (size_t)kVecPerBlock * (E + 1) * sizeof(int) : 0;
