@@ -694,7 +694,9 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // whatever the quantize stage has not already produced
     const bool need_ra_vm = ra_vm && !ra_vm_done, need_rb_vm = rb_vm && !rb_vm_done;
     const bool need_rb_em = rb_em && !rb_em_done;
-    if (need_ra_vm || ra_em)
+    if (ra_em && !need_ra_vm && rows_resid_em_ok(A, M, K, lda, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M))
+      SRQ_HIP(h, launch_rows_resid_em(A, M, K, lda, qmax, trunc, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M, st));
+    else if (need_ra_vm || ra_em)
       SRQ_HIP(h, launch_residual_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, p.lam_ra, qmax, trunc,
                                        need_ra_vm ? p.RA_int : nullptr, Kc, ra_em ? p.RA_em : nullptr, M, st));
     if (need_rb_vm || need_rb_em) {

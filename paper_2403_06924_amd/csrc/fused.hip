@@ -269,6 +269,56 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
   }
 }
 
+// ---- k-major residual codes of the row-scaled operand (RA as K x M, read by the vector-ALU
+// execution of the second correction term): the 16-row x 4-column patches of cols_pass_kernel
+// with the scales taken per row, so that the sixteen codes of one k go out as one 16-byte store.
+__global__ __launch_bounds__(256) void rows_resid_em_kernel(const float* __restrict__ X, int64_t rows,
+                                                            int64_t cols, int64_t ldx, float qmax, int trunc,
+                                                            const float* __restrict__ scale,
+                                                            const float* __restrict__ lambda,
+                                                            const float* __restrict__ rlambda,
+                                                            int8_t* __restrict__ Rem, int64_t ldem) {
+  const int cg = threadIdx.x & 15, rb = threadIdx.x >> 4;
+  const int64_t col0 = (int64_t)blockIdx.x * 64 + cg * 4;
+  const int64_t row0 = (int64_t)blockIdx.y * 256 + rb * 16;     // rows is a multiple of 16
+  if (col0 >= cols || row0 >= rows) return;
+  float sc[16], lam[16], rlam[16];
+#pragma unroll
+  for (int i = 0; i < 16; i += 4) {
+    const float4 a = *reinterpret_cast<const float4*>(scale + row0 + i);
+    const float4 b = *reinterpret_cast<const float4*>(lambda + row0 + i);
+    const float4 c = *reinterpret_cast<const float4*>(rlambda + row0 + i);
+    sc[i] = a.x; sc[i + 1] = a.y; sc[i + 2] = a.z; sc[i + 3] = a.w;
+    lam[i] = b.x; lam[i + 1] = b.y; lam[i + 2] = b.z; lam[i + 3] = b.w;
+    rlam[i] = c.x; rlam[i + 1] = c.y; rlam[i + 2] = c.z; rlam[i + 3] = c.w;
+  }
+  float4 v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = load_streaming(reinterpret_cast<const float4*>(X + (row0 + i) * ldx + col0));
+  unsigned packed[4][4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int wd = 0; wd < 4; ++wd) packed[c][wd] = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const float xv[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int q = quant_code(xv[c], lam[i], qmax, trunc);
+      const float res = xv[c] - (float)q * sc[i];
+      const int code = quant_code(res, rlam[i], qmax, trunc);
+      packed[c][i >> 2] |= (unsigned)(code & 0xff) << (8 * (i & 3));
+    }
+  }
+  typedef unsigned u4v __attribute__((ext_vector_type(4)));
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    u4v pk = {packed[c][0], packed[c][1], packed[c][2], packed[c][3]};
+    __builtin_nontemporal_store(pk, reinterpret_cast<u4v*>(Rem + (col0 + c) * ldem + row0));
+  }
+}
+
 // ---- keep-mask of an operand with contiguous vectors (A): one block per row ------------------
 // Generic version: one 64-bit word per wave iteration via ballot.
 __global__ __launch_bounds__(256) void rows_mask_kernel(const float* __restrict__ X, int64_t cols, int64_t ldx,
@@ -476,6 +526,21 @@ hipError_t launch_rows_fused(const float* X, int64_t rows, int64_t cols, int64_t
   else if (cols <= 8192) SRQ_ROWS(8);
   else SRQ_ROWS(16);
 #undef SRQ_ROWS
+  return hipGetLastError();
+}
+
+bool rows_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* scale,
+                      const float* lambda, const float* rlambda, const int8_t* Rem, int64_t ldem) {
+  return rows > 0 && cols > 0 && (rows % 16) == 0 && (cols % 4) == 0 && (ldx % 4) == 0 && (ldem % 16) == 0 &&
+         aligned16(X) && aligned16(scale) && aligned16(lambda) && aligned16(rlambda) && aligned16(Rem);
+}
+
+hipError_t launch_rows_resid_em(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                                const float* scale, const float* lambda, const float* rlambda, int8_t* Rem,
+                                int64_t ldem, hipStream_t st) {
+  dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 255) / 256));
+  hipLaunchKernelGGL(rows_resid_em_kernel, grid, dim3(256), 0, st, X, rows, cols, ldx, (float)qmax, trunc, scale,
+                     lambda, rlambda, Rem, ldem);
   return hipGetLastError();
 }
 

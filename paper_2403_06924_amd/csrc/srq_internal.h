@@ -91,6 +91,11 @@ bool rows_fused_ok(const float* X, int64_t cols, int64_t ldx, const int8_t* Q, i
 hipError_t launch_rows_fused(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                              int8_t* Q, int64_t ldq, float* scale, float* lambda, int8_t* Rq, int64_t ldr,
                              float* rscale, float* rlambda, hipStream_t st);
+bool rows_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* scale,
+                      const float* lambda, const float* rlambda, const int8_t* Rem, int64_t ldem);
+hipError_t launch_rows_resid_em(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                                const float* scale, const float* lambda, const float* rlambda, int8_t* Rem,
+                                int64_t ldem, hipStream_t st);
 bool cols_pass_ok(const float* X, int64_t cols, int64_t ldx);
 hipError_t launch_cols_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, uint32_t* amax_bits,
                             hipStream_t st);
