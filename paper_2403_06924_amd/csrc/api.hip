@@ -636,12 +636,14 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
                                 (term_b && fastB) ? p.tot_b : nullptr, N, p.b_ptr, p.nnz + 1, st));
     // line 9 and the branch of line 11: which execution each term takes
     const bool sync_mode = strategy == SRQ_STRATEGY_AUTO || dense_fallback_density <= 1.f;
+    int64_t known_a = -1, known_b = -1;        // kept entries, once the host has read them
     if (sync_mode) {
       h->host_nnz[0] = h->host_nnz[1] = 0;
       SRQ_HIP(h, hipMemcpyAsync(h->host_nnz, p.nnz, 2 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
       SRQ_HIP(h, hipStreamSynchronize(st));
       int64_t na = term_a ? h->host_nnz[0] : 0, nb = term_b ? h->host_nnz[1] : 0;
       double da = (double)na / ((double)M * (double)K), db = (double)nb / ((double)N * (double)K);
+      known_a = na; known_b = nb;
       auto pick = [&](double d, double crossover) {
         if (d >= (double)dense_fallback_density) return 3;
         if (strategy == SRQ_STRATEGY_AUTO) return d >= crossover ? 2 : 1;
@@ -668,7 +670,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       im.a_ptr = p.a_ptr; im.capacity_a = p.cap_a;
       if (path_a != 3) {
         SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, Kc, p.a_ptr, p.a_idx, p.a_val, p.cap_a,
-                                       path_a == 2 ? p.Ad : nullptr, Kc, st));
+                                       path_a == 2 ? p.Ad : nullptr, Kc, known_a, st));
         im.a_idx = p.a_idx; im.a_val = p.a_val;
       }
     }
@@ -677,7 +679,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     } else if (term_b) {
       if (fastB) {
         SRQ_HIP(h, launch_scatter_mask(p.mask_b, N, K, p.B_int, Kc, p.b_ptr, p.b_idx, p.b_val, p.cap_b,
-                                       path_b == 2 ? p.Bd : nullptr, Kc, st));
+                                       path_b == 2 ? p.Bd : nullptr, Kc, known_b, st));
       } else {
         SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
                                          p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));

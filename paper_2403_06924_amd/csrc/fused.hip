@@ -391,6 +391,9 @@ __global__ __launch_bounds__(256) void rows_mask_vec_kernel(const float* __restr
 // neighbouring slots of idx / val at any density.  Optionally the vector is also written
 // expanded to zero-filled dense codes (operand of the matrix-core execution of the sparse
 // product), from the same registers.
+template <bool SKIP>   // SKIP: for operands that keep well under one entry per 256 elements and
+                       // need no expansion; a wave looks at the mask first and leaves the codes
+                       // of a chunk without kept entries unread
 __global__ __launch_bounds__(256) void scatter_mask_kernel(const uint64_t* __restrict__ mask, int64_t words,
                                                            int64_t veclen, const int8_t* __restrict__ Q,
                                                            int64_t ldq, const int32_t* __restrict__ ptr,
@@ -427,6 +430,10 @@ __global__ __launch_bounds__(256) void scatter_mask_kernel(const uint64_t* __res
   for (int64_t c = c0; c < c1; ++c) {
     const int64_t e = c * 256 + 4 * lane;
     unsigned nib = 0, code = 0;
+    if (SKIP) {
+      if (e < veclen) nib = (mv32[e >> 5] >> (e & 31)) & 0xfu;   // the tail is masked below
+      if (!__ballot(nib != 0)) continue;
+    }
     if (e < veclen) {
       nib = (mv32[e >> 5] >> (e & 31)) & 0xfu;
       const int64_t left = veclen - e;
@@ -641,10 +648,16 @@ hipError_t launch_rows_mask(const float* X, int64_t rows, int64_t cols, int64_t 
 
 hipError_t launch_scatter_mask(const uint64_t* mask, int64_t nvec, int64_t veclen, const int8_t* Q, int64_t ldq,
                                const int32_t* ptr, int32_t* idx, int8_t* val, int64_t capacity, int8_t* dense,
-                               int64_t ldd, hipStream_t st) {
+                               int64_t ldd, int64_t nnz_hint, hipStream_t st) {
   if (nvec <= 0 || veclen <= 0) return hipSuccess;
-  hipLaunchKernelGGL(scatter_mask_kernel, dim3((unsigned)nvec), dim3(256), 0, st, mask, mask_words(veclen),
-                     veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd);
+  // measured at 8192 x 8192: skipping empty chunks pays below about one kept entry per 512
+  if (!dense && nnz_hint >= 0 && (double)nnz_hint * 512.0 < (double)nvec * (double)veclen) {
+    hipLaunchKernelGGL(scatter_mask_kernel<true>, dim3((unsigned)nvec), dim3(256), 0, st, mask,
+                       mask_words(veclen), veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd);
+  } else {
+    hipLaunchKernelGGL(scatter_mask_kernel<false>, dim3((unsigned)nvec), dim3(256), 0, st, mask,
+                       mask_words(veclen), veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd);
+  }
   return hipGetLastError();
 }
 

@@ -122,10 +122,12 @@ hipError_t launch_cols_mask(const float* X, int64_t rows, int64_t cols, int64_t 
                             uint64_t* mask, int32_t* counts, hipStream_t st);
 hipError_t launch_rows_mask(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* thresh,
                             uint64_t* mask, int32_t* counts, hipStream_t st);
-// compaction from mask + codes; dense != null also writes the vector zero-filled to dense[v*ldd + e]
+// compaction from mask + codes; dense != null also writes the vector zero-filled to dense[v*ldd + e];
+// nnz_hint: the number of kept entries if the host knows it (picks the variant for very sparse
+// operands), else -1
 hipError_t launch_scatter_mask(const uint64_t* mask, int64_t nvec, int64_t veclen, const int8_t* Q, int64_t ldq,
                                const int32_t* ptr, int32_t* idx, int8_t* val, int64_t capacity, int8_t* dense,
-                               int64_t ldd, hipStream_t st);
+                               int64_t ldd, int64_t nnz_hint, hipStream_t st);
 // two exclusive scans in one launch; a null totals pointer skips that half
 hipError_t launch_scan_pair(const int32_t* t0, int64_t n0, int32_t* p0, int64_t* z0, const int32_t* t1,
                             int64_t n1, int32_t* p1, int64_t* z1, hipStream_t st);

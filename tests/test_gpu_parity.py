@@ -315,6 +315,21 @@ def test_ragged_shapes_all_strategies(srq, b, name, shape, strategy):
     check_against_oracle(srq, b, A, B, ta, tb, strategy=strategy)
 
 
+@pytest.mark.parametrize("shape", [(300, 200, 2048), (257, 129, 1531), (64, 96, 4100)])
+@pytest.mark.parametrize("density", [1e-3, 2e-4])
+def test_very_sparse_operands_auto(srq, b, shape, density):
+    """Well under one kept entry per 512 elements, host-synchronising mode: the compaction takes the
+    variant that leaves the codes of empty 256-element chunks unread (ragged tails included)."""
+    A, B = wl.make_inputs("C2", *shape)
+    plain = o.quantized_product(A, B)
+    drow, dcol = o.abs_means(plain.D_F)
+    ta = wl.theta_for_density(A, drow, "row", density)
+    tb = wl.theta_for_density(B, dcol, "col", density)
+    ref, _, st = check_against_oracle(srq, b, A, B, ta, tb, strategy=0)
+    assert 0 < ref.csr_a.nnz * 512 < A.size and 0 < ref.csc_b.nnz * 512 < B.size
+    assert st["path_a"] == 1 and st["path_b"] == 1
+
+
 def test_bounds_theta_inf_and_zero(srq, b):
     A, B = wl.make_inputs("C2", 200, 136, 300)
     inf = float("inf")
