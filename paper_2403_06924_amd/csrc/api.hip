@@ -532,7 +532,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   const bool global_scale = h->scale_mode == SRQ_SCALE_GLOBAL;
   const bool fastA = K > 0 && !global_scale && rows_fused_ok(A, K, lda, p.A_int, Kc, p.RA_int, Kc);
   const bool fastB = K > 0 && !global_scale && cols_pass_ok(B, N, ldb);
-  bool ra_vm_done = false, rb_vm_done = false, rb_em_done = false;
+  bool ra_vm_done = false, ra_em_done = false, rb_vm_done = false, rb_em_done = false;
+  bool rb_in_select = false, rb_want_em = false;   // residual codes of B left to the selection pass
   // lines 1: Quant.  amax per vector -> scale, lambda -> codes (and max |residual| per vector)
   {
   StageTimer tm(h, st, SRQ_STAGE_QUANTIZE);
@@ -577,9 +578,13 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       const bool want_em = term_a && dense_fallback_density > 1.f &&
                            (strategy == SRQ_STRATEGY_CSR_VALU ||
                             (strategy == SRQ_STRATEGY_AUTO && h->last_path_a == SRQ_STRATEGY_CSR_VALU));
-      SRQ_HIP(h, launch_cols_resid_from_amax(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.ramax_b, p.s_rb,
-                                             p.lam_rb, want_em ? nullptr : p.RB_int, Kc,
-                                             want_em ? p.RB_em : nullptr, N, st));
+      // when B's selection pass will run it writes these codes too (one read of B less)
+      rb_in_select = term_b;
+      rb_want_em = want_em;
+      if (!rb_in_select)
+        SRQ_HIP(h, launch_cols_resid_from_amax(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.ramax_b, p.s_rb,
+                                               p.lam_rb, want_em ? nullptr : p.RB_int, Kc,
+                                               want_em ? p.RB_em : nullptr, N, st));
       rb_vm_done = !want_em;
       rb_em_done = want_em;
     }
@@ -623,10 +628,31 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     im.drow = p.drow; im.dcol = p.dcol; im.t_a = p.t_a; im.t_b = p.t_b;
     // lines 8-10: Reduce.  Keep-bits and per-vector counts, then the prefix scans
     int64_t chk = select_chunks(K);
-    if (term_a) SRQ_HIP(h, launch_rows_mask(A, M, K, lda, p.t_a, p.mask_a, p.tot_a, st));
+    if (term_a) {
+      // if term 2 is expected on the vector ALUs (fixed by the caller, or where SRQ_STRATEGY_AUTO
+      // ended up in the previous call), A's selection pass also writes the k-major residual
+      // codes that execution reads: one read of A less
+      const bool want_ra_em = term_b && dense_fallback_density > 1.f &&
+                              (strategy == SRQ_STRATEGY_CSR_VALU ||
+                               (strategy == SRQ_STRATEGY_AUTO && h->last_path_b == SRQ_STRATEGY_CSR_VALU)) &&
+                              rows_mask_resid_em_ok(A, M, K, lda, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M, p.t_a);
+      if (want_ra_em) {
+        SRQ_HIP(h, launch_rows_mask_resid_em(A, M, K, lda, qmax, trunc, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M,
+                                             p.t_a, p.mask_a, p.tot_a, st));
+        ra_em_done = true;
+      } else {
+        SRQ_HIP(h, launch_rows_mask(A, M, K, lda, p.t_a, p.mask_a, p.tot_a, st));
+      }
+    }
     if (term_b) {
       if (fastB) {
-        SRQ_HIP(h, launch_cols_mask(B, K, N, ldb, p.t_b, p.mask_b, p.tot_b, st));   // tot_b cleared in the quantize stage
+        // (tot_b was cleared in the quantize stage)
+        if (rb_in_select)
+          SRQ_HIP(h, launch_cols_mask_resid(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.ramax_b, p.s_rb, p.lam_rb,
+                                            rb_want_em ? nullptr : p.RB_int, Kc, rb_want_em ? p.RB_em : nullptr,
+                                            N, p.t_b, p.mask_b, p.tot_b, st));
+        else
+          SRQ_HIP(h, launch_cols_mask(B, K, N, ldb, p.t_b, p.mask_b, p.tot_b, st));
       } else {
         SRQ_HIP(h, launch_select_count(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.cnt_b, st));
         SRQ_HIP(h, launch_select_scan(p.cnt_b, N, chk, p.tot_b, p.b_ptr, p.nnz + 1, st));
@@ -654,6 +680,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       if (term_a) path_a = pick(da, K > 8192 ? kAutoMfmaDensityALongK : kAutoMfmaDensityA);
       if (term_b) path_b = pick(db, K > 8192 ? kAutoMfmaDensityBLongK : kAutoMfmaDensityB);
       if (term_a && strategy == SRQ_STRATEGY_AUTO) h->last_path_a = path_a;
+      if (term_b && strategy == SRQ_STRATEGY_AUTO) h->last_path_b = path_b;
       // an operand on the dense branch is not compacted, so only the others need room
       if ((path_a != 3 && na > p.cap_a) || (path_b != 3 && nb > p.cap_b)) {
         if (stats_dev) SRQ_HIP(h, launch_stats(term_a ? p.nnz : nullptr, term_b ? p.nnz + 1 : nullptr, 0, 0, stats_dev, st));
@@ -695,12 +722,13 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     StageTimer tm(h, st, SRQ_STAGE_RESIDUAL);
     // whatever the quantize stage has not already produced
     const bool need_ra_vm = ra_vm && !ra_vm_done, need_rb_vm = rb_vm && !rb_vm_done;
-    const bool need_rb_em = rb_em && !rb_em_done;
-    if (ra_em && !need_ra_vm && rows_resid_em_ok(A, M, K, lda, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M))
+    const bool need_rb_em = rb_em && !rb_em_done, need_ra_em = ra_em && !ra_em_done;
+    if (need_ra_em && !need_ra_vm && rows_resid_em_ok(A, M, K, lda, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M))
       SRQ_HIP(h, launch_rows_resid_em(A, M, K, lda, qmax, trunc, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M, st));
-    else if (need_ra_vm || ra_em)
+    else if (need_ra_vm || need_ra_em)
       SRQ_HIP(h, launch_residual_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, p.lam_ra, qmax, trunc,
-                                       need_ra_vm ? p.RA_int : nullptr, Kc, ra_em ? p.RA_em : nullptr, M, st));
+                                       need_ra_vm ? p.RA_int : nullptr, Kc, need_ra_em ? p.RA_em : nullptr, M,
+                                       st));
     if (need_rb_vm || need_rb_em) {
       if (fastB)
         SRQ_HIP(h, launch_cols_resid(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.lam_rb,

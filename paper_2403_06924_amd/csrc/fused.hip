@@ -11,7 +11,12 @@
 //                       INT8 output is written 16 bytes at a time without going through LDS.
 //   *_mask_kernel       threshold compare of Eq. avgQuan -> one keep-bit per element (the only
 //                       pass that has to re-read FP32 after the first product) + per-vector
-//                       counts.
+//                       counts.  Inside the whole-path call the residual codes whose layout is
+//                       only needed after the selection come out of this read as well: B's
+//                       third pass is the selection pass (cols_pass_kernel<kColsMaskResid>),
+//                       and the k-major residual codes of A are written by A's selection pass
+//                       when the vector ALUs will run the second term
+//                       (rows_resid_em_kernel<true>).
 //   scatter_mask_kernel compaction to CSR / CSC from the bit mask and the INT8 codes.
 #include "srq_internal.h"
 
@@ -106,7 +111,11 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
 // ---- operand with strided vectors (B, columns of a row-major matrix) ------------------------
 // A block covers 256 rows x 64 columns; thread (cg, rb) holds rows rb*16..rb*16+15 of the four
 // columns cg*4..cg*4+3.
-enum ColsMode { kColsAmax = 0, kColsCodes = 1, kColsResid = 2, kColsMask = 3 };
+// (kColsMaskResid: the selection pass also writes the residual codes, so that B is read three
+// times per call and not four)
+enum ColsMode { kColsAmax = 0, kColsCodes = 1, kColsResid = 2, kColsMask = 3, kColsMaskResid = 4 };
+constexpr bool cols_resid(int mode) { return mode == kColsResid || mode == kColsMaskResid; }
+constexpr bool cols_mask(int mode) { return mode == kColsMask || mode == kColsMaskResid; }
 
 template <int MODE>
 __global__ __launch_bounds__(256) void cols_pass_kernel(
@@ -135,7 +144,7 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
     int64_t r = row0 + i;
     const float4* src = reinterpret_cast<const float4*>(X + r * ldx + col0);
     const bool ok = colok && r < rows;
-    if (MODE == kColsResid || MODE == kColsMask) v[i] = ok ? load_streaming(src) : make_float4(0.f, 0.f, 0.f, 0.f);
+    if (cols_resid(MODE) || cols_mask(MODE)) v[i] = ok ? load_streaming(src) : make_float4(0.f, 0.f, 0.f, 0.f);
     else v[i] = ok ? *src : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   if (MODE == kColsAmax) {
@@ -154,7 +163,7 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
     }
     return;
   }
-  if (MODE == kColsMask) {
+  if (cols_mask(MODE)) {
     float4 t = colok ? *reinterpret_cast<const float4*>(thresh + col0) : make_float4(0.f, 0.f, 0.f, 0.f);
     const float tt[4] = {t.x, t.y, t.z, t.w};
     unsigned bits[4] = {0, 0, 0, 0};
@@ -178,7 +187,7 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
       int64_t col = (int64_t)blockIdx.x * 64 + threadIdx.x;
       if (col < cols && red[threadIdx.x]) atomicAdd(&counts[col], (int32_t)red[threadIdx.x]);
     }
-    return;
+    if (MODE == kColsMask) return;
   }
   // codes / residual codes
   float lam[4] = {0.f, 0.f, 0.f, 0.f}, sc[4] = {0.f, 0.f, 0.f, 0.f}, rlam[4] = {0.f, 0.f, 0.f, 0.f};
@@ -201,7 +210,7 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
     lam[0] = l4.x; lam[1] = l4.y; lam[2] = l4.z; lam[3] = l4.w;
     sc[0] = s4.x; sc[1] = s4.y; sc[2] = s4.z; sc[3] = s4.w;
   }
-  if (MODE == kColsResid && colok) {
+  if (cols_resid(MODE) && colok) {
     if (amax_in) {
       const uint4 a4 = *reinterpret_cast<const uint4*>(amax_in + col0);
       const float am[4] = {__uint_as_float(a4.x), __uint_as_float(a4.y), __uint_as_float(a4.z), __uint_as_float(a4.w)};
@@ -272,12 +281,18 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
 // ---- k-major residual codes of the row-scaled operand (RA as K x M, read by the vector-ALU
 // execution of the second correction term): the 16-row x 4-column patches of cols_pass_kernel
 // with the scales taken per row, so that the sixteen codes of one k go out as one 16-byte store.
+// MASK: the pass is also the selection pass of the operand (threshold compare per row; cols is
+// then a multiple of 64): the sixteen lanes that share a row assemble its 64 keep-bits with
+// shuffles.  The per-row counts are taken from the mask afterwards (mask_count_kernel).
+template <bool MASK>
 __global__ __launch_bounds__(256) void rows_resid_em_kernel(const float* __restrict__ X, int64_t rows,
                                                             int64_t cols, int64_t ldx, float qmax, int trunc,
                                                             const float* __restrict__ scale,
                                                             const float* __restrict__ lambda,
                                                             const float* __restrict__ rlambda,
-                                                            int8_t* __restrict__ Rem, int64_t ldem) {
+                                                            int8_t* __restrict__ Rem, int64_t ldem,
+                                                            const float* __restrict__ thresh,
+                                                            uint8_t* __restrict__ mask, int64_t mask_stride) {
   const int cg = threadIdx.x & 15, rb = threadIdx.x >> 4;
   const int64_t col0 = (int64_t)blockIdx.x * 64 + cg * 4;
   const int64_t row0 = (int64_t)blockIdx.y * 256 + rb * 16;     // rows is a multiple of 16
@@ -295,6 +310,25 @@ __global__ __launch_bounds__(256) void rows_resid_em_kernel(const float* __restr
   float4 v[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) v[i] = load_streaming(reinterpret_cast<const float4*>(X + (row0 + i) * ldx + col0));
+  if (MASK) {
+#pragma unroll
+    for (int i = 0; i < 16; i += 4) {
+      const float4 t4 = *reinterpret_cast<const float4*>(thresh + row0 + i);
+      const float tt[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float4 x = v[i + j];
+        const float t = tt[j];
+        const unsigned nib = (fabsf(x.x) > t ? 1u : 0u) | (fabsf(x.y) > t ? 2u : 0u) |
+                             (fabsf(x.z) > t ? 4u : 0u) | (fabsf(x.w) > t ? 8u : 0u);
+        // (all sixteen lanes of a row are active together: cols is a multiple of 64)
+        const unsigned b8 = nib | (__shfl_down(nib, 1, 64) << 4);
+        const unsigned b16 = b8 | (__shfl_down(b8, 2, 64) << 8);
+        const unsigned b32 = b16 | (__shfl_down(b16, 4, 64) << 16);
+        if (!(cg & 7)) *reinterpret_cast<unsigned*>(mask + (row0 + i + j) * mask_stride + (col0 >> 3)) = b32;
+      }
+    }
+  }
   unsigned packed[4][4];
 #pragma unroll
   for (int c = 0; c < 4; ++c)
@@ -317,6 +351,18 @@ __global__ __launch_bounds__(256) void rows_resid_em_kernel(const float* __restr
     u4v pk = {packed[c][0], packed[c][1], packed[c][2], packed[c][3]};
     __builtin_nontemporal_store(pk, reinterpret_cast<u4v*>(Rem + (col0 + c) * ldem + row0));
   }
+}
+
+// kept entries per vector from a finished mask: one wave per vector
+__global__ __launch_bounds__(256) void mask_count_kernel(const uint64_t* __restrict__ mask, int64_t words,
+                                                         int64_t nvec, int32_t* __restrict__ counts) {
+  const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (v >= nvec) return;
+  const int lane = threadIdx.x & 63;
+  int total = 0;
+  for (int64_t wd = lane; wd < words; wd += 64) total += __popcll(mask[v * words + wd]);
+  for (int off = 32; off > 0; off >>= 1) total += __shfl_xor(total, off, 64);
+  if (lane == 0) counts[v] = total;
 }
 
 // ---- keep-mask of an operand with contiguous vectors (A): one block per row ------------------
@@ -546,8 +592,32 @@ hipError_t launch_rows_resid_em(const float* X, int64_t rows, int64_t cols, int6
                                 const float* scale, const float* lambda, const float* rlambda, int8_t* Rem,
                                 int64_t ldem, hipStream_t st) {
   dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 255) / 256));
-  hipLaunchKernelGGL(rows_resid_em_kernel, grid, dim3(256), 0, st, X, rows, cols, ldx, (float)qmax, trunc, scale,
-                     lambda, rlambda, Rem, ldem);
+  hipLaunchKernelGGL(rows_resid_em_kernel<false>, grid, dim3(256), 0, st, X, rows, cols, ldx, (float)qmax, trunc,
+                     scale, lambda, rlambda, Rem, ldem, nullptr, nullptr, 0);
+  return hipGetLastError();
+}
+
+// the same pass doubling as the selection pass of the operand: keep-mask (mask_words(cols) words
+// per row) and per-row counts as launch_rows_mask leaves them
+bool rows_mask_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* scale,
+                           const float* lambda, const float* rlambda, const int8_t* Rem, int64_t ldem,
+                           const float* thresh) {
+  return rows_resid_em_ok(X, rows, cols, ldx, scale, lambda, rlambda, Rem, ldem) && (cols % 64) == 0 &&
+         aligned16(thresh);
+}
+
+hipError_t launch_rows_mask_resid_em(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                                     const float* scale, const float* lambda, const float* rlambda, int8_t* Rem,
+                                     int64_t ldem, const float* thresh, uint64_t* mask, int32_t* counts,
+                                     hipStream_t st) {
+  dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 255) / 256));
+  hipLaunchKernelGGL(rows_resid_em_kernel<true>, grid, dim3(256), 0, st, X, rows, cols, ldx, (float)qmax, trunc,
+                     scale, lambda, rlambda, Rem, ldem, thresh, reinterpret_cast<uint8_t*>(mask),
+                     mask_words(cols) * 8);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(mask_count_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, mask, mask_words(cols),
+                     rows, counts);
   return hipGetLastError();
 }
 
@@ -618,6 +688,19 @@ hipError_t launch_cols_mask(const float* X, int64_t rows, int64_t cols, int64_t 
   hipLaunchKernelGGL(cols_pass_kernel<kColsMask>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      0.f, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, thresh, nullptr, nullptr, 0,
                      nullptr, 0, reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts);
+  return hipGetLastError();
+}
+
+// selection pass that also writes the residual codes (scales derived as in launch_cols_resid_from_amax)
+hipError_t launch_cols_mask_resid(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                                  const float* scale, const float* lambda, const uint32_t* ramax_bits,
+                                  float* rscale, float* rlambda, int8_t* Rvm, int64_t ldvm, int8_t* Rem,
+                                  int64_t ldem, const float* thresh, uint64_t* mask, int32_t* counts,
+                                  hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  hipLaunchKernelGGL(cols_pass_kernel<kColsMaskResid>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols,
+                     ldx, (float)qmax, trunc, scale, lambda, nullptr, ramax_bits, rscale, rlambda, thresh, nullptr,
+                     Rvm, ldvm, Rem, ldem, reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts);
   return hipGetLastError();
 }
 

@@ -20,6 +20,7 @@ struct srq_context {
   int prof_created;
   int scale_mode;        // srq_scale_t of the next srq_compensated_gemm calls
   int last_path_a;       // execution SRQ_STRATEGY_AUTO chose for term 1 in the previous call (0: none yet)
+  int last_path_b;       // the same for term 2
 };
 
 namespace srq {
@@ -96,6 +97,14 @@ bool rows_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, c
 hipError_t launch_rows_resid_em(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                                 const float* scale, const float* lambda, const float* rlambda, int8_t* Rem,
                                 int64_t ldem, hipStream_t st);
+// that pass doubling as the selection pass of the operand (mask and counts as launch_rows_mask)
+bool rows_mask_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* scale,
+                           const float* lambda, const float* rlambda, const int8_t* Rem, int64_t ldem,
+                           const float* thresh);
+hipError_t launch_rows_mask_resid_em(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                                     const float* scale, const float* lambda, const float* rlambda, int8_t* Rem,
+                                     int64_t ldem, const float* thresh, uint64_t* mask, int32_t* counts,
+                                     hipStream_t st);
 bool cols_pass_ok(const float* X, int64_t cols, int64_t ldx);
 hipError_t launch_cols_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, uint32_t* amax_bits,
                             hipStream_t st);
@@ -120,6 +129,11 @@ hipError_t launch_cols_resid(const float* X, int64_t rows, int64_t cols, int64_t
                              int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st);
 hipError_t launch_cols_mask(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* thresh,
                             uint64_t* mask, int32_t* counts, hipStream_t st);
+hipError_t launch_cols_mask_resid(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
+                                  const float* scale, const float* lambda, const uint32_t* ramax_bits,
+                                  float* rscale, float* rlambda, int8_t* Rvm, int64_t ldvm, int8_t* Rem,
+                                  int64_t ldem, const float* thresh, uint64_t* mask, int32_t* counts,
+                                  hipStream_t st);
 hipError_t launch_rows_mask(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* thresh,
                             uint64_t* mask, int32_t* counts, hipStream_t st);
 // compaction from mask + codes; dense != null also writes the vector zero-filled to dense[v*ldd + e];

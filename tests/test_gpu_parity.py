@@ -330,6 +330,20 @@ def test_very_sparse_operands_auto(srq, b, shape, density):
     assert st["path_a"] == 1 and st["path_b"] == 1
 
 
+def test_auto_repeated_calls_reuse_the_previous_choice(srq, b):
+    """With SRQ_STRATEGY_AUTO the layouts written ahead of the host's decision follow the previous
+    call's choice (selection passes that also write residual codes); every call in a sequence that
+    moves between the vector-ALU and the matrix-core regime must still match the oracle."""
+    A, B = wl.make_inputs("C2", 256, 192, 512)
+    plain = o.quantized_product(A, B)
+    drow, dcol = o.abs_means(plain.D_F)
+    for density in (1e-3, 1e-3, 0.2, 0.2, 1e-3, 1e-3):
+        ta = wl.theta_for_density(A, drow, "row", density)
+        tb = wl.theta_for_density(B, dcol, "col", density)
+        _, _, st = check_against_oracle(srq, b, A, B, ta, tb, strategy=0)
+        assert st["path_a"] == st["path_b"] == (1 if density < 0.005 else 2)
+
+
 def test_bounds_theta_inf_and_zero(srq, b):
     A, B = wl.make_inputs("C2", 200, 136, 300)
     inf = float("inf")
