@@ -619,32 +619,30 @@ __global__ __launch_bounds__(1024) void scan_pair_kernel(const int32_t* t0, int6
   int32_t* ptr = blockIdx.x == 0 ? p0 : p1;
   int64_t* nnz_dev = blockIdx.x == 0 ? z0 : z1;
   if (!totals) return;
+  // thread t owns the `per` consecutive vectors from t * per on: one block-wide scan of the
+  // per-thread sums, whatever the length
   __shared__ int64_t wave_sum[16];
-  __shared__ int64_t carry_s;
-  int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  if (tid == 0) carry_s = 0;
-  __syncthreads();
-  for (int64_t base = 0; base < nvec; base += 1024) {
-    int64_t v = base + tid;
-    int64_t x = v < nvec ? totals[v] : 0;
-    int64_t inc = x;
-    for (int d = 1; d < 64; d <<= 1) {
-      int64_t y = __shfl_up(inc, d, 64);
-      if (lane >= d) inc += y;
-    }
-    if (lane == 63) wave_sum[w] = inc;
-    __syncthreads();
-    int64_t wave_off = 0;
-    for (int i = 0; i < w; ++i) wave_off += wave_sum[i];
-    int64_t carry = carry_s;
-    if (v < nvec) ptr[v] = (int32_t)(carry + wave_off + inc - x);
-    __syncthreads();
-    if (tid == 1023) carry_s = carry + wave_off + inc;
-    __syncthreads();
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int64_t per = (nvec + 1023) / 1024;
+  const int64_t v0 = tid * per, v1 = v0 + per < nvec ? v0 + per : nvec;
+  int64_t x = 0;
+  for (int64_t v = v0; v < v1; ++v) x += totals[v];
+  int64_t inc = x;
+  for (int d = 1; d < 64; d <<= 1) {
+    int64_t y = __shfl_up(inc, d, 64);
+    if (lane >= d) inc += y;
   }
-  if (tid == 0) {
-    ptr[nvec] = (int32_t)carry_s;
-    if (nnz_dev) *nnz_dev = carry_s;
+  if (lane == 63) wave_sum[w] = inc;
+  __syncthreads();
+  int64_t run = inc - x;                              // exclusive prefix of this thread's span
+  for (int i = 0; i < w; ++i) run += wave_sum[i];
+  for (int64_t v = v0; v < v1; ++v) {
+    ptr[v] = (int32_t)run;
+    run += totals[v];
+  }
+  if (tid == 1023) {
+    ptr[nvec] = (int32_t)run;
+    if (nnz_dev) *nnz_dev = run;
   }
 }
 
