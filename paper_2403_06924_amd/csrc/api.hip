@@ -546,9 +546,16 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   }
   // operand A: vectors are contiguous rows
   if (fastA) {
+    // the K-contiguous residual codes of A feed the matrix-core executions of term 2; when that
+    // term is expected on the vector ALUs (same prediction as for B's layouts below) only the
+    // residual scales are produced here and A's selection pass writes the k-major codes
+    const bool skip_ra_vm = comp && term_b && dense_fallback_density > 1.f &&
+                            (strategy == SRQ_STRATEGY_CSR_VALU ||
+                             (strategy == SRQ_STRATEGY_AUTO && h->last_path_b == SRQ_STRATEGY_CSR_VALU));
     SRQ_HIP(h, launch_rows_fused(A, M, K, lda, qmax, trunc, p.A_int, Kc, p.s_a, p.lam_a,
-                                 comp ? p.RA_int : nullptr, Kc, p.s_ra, p.lam_ra, st));
-    ra_vm_done = comp;
+                                 (comp && !skip_ra_vm) ? p.RA_int : nullptr, Kc, comp ? p.s_ra : nullptr,
+                                 comp ? p.lam_ra : nullptr, st));
+    ra_vm_done = comp && !skip_ra_vm;
   } else {
     SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_a), M, 0, st));
     if (comp) SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_ra), M, 0, st));

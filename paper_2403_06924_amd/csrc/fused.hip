@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
     int q0 = quant_code(x[i].x, lam, qmax, trunc), q1 = quant_code(x[i].y, lam, qmax, trunc);
     int q2 = quant_code(x[i].z, lam, qmax, trunc), q3 = quant_code(x[i].w, lam, qmax, trunc);
     if (c4 < n4) __builtin_nontemporal_store(pack4(q0, q1, q2, q3), &qdst[c4]);
-    if (Rq) {
+    if (rscale) {
       // residual r = fl(x - fl(float(q) * s)); kept in place of x
       x[i].x = x[i].x - (float)q0 * s; x[i].y = x[i].y - (float)q1 * s;
       x[i].z = x[i].z - (float)q2 * s; x[i].w = x[i].w - (float)q3 * s;
@@ -91,10 +91,12 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
     }
   }
   if (threadIdx.x == 0) { scale[row] = s; lambda[row] = lam; }
-  if (!Rq) return;
+  if (!rscale) return;
   const float ramax = block_max_256(rm, sm);
   float rlam = 0.f, rs = 0.f;
   if (ramax > 0.f) { rlam = qmax / ramax; rs = ramax / qmax; }
+  if (threadIdx.x == 0) { rscale[row] = rs; rlambda[row] = rlam; }
+  if (!Rq) return;                                   // residual scales only: the codes are written elsewhere
   unsigned* rdst = reinterpret_cast<unsigned*>(Rq + row * ldr);
 #pragma unroll
   for (int i = 0; i < NV4; ++i) {
@@ -105,7 +107,6 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
                                         quant_code(x[i].z, rlam, qmax, trunc), quant_code(x[i].w, rlam, qmax, trunc)),
                                   &rdst[c4]);
   }
-  if (threadIdx.x == 0) { rscale[row] = rs; rlambda[row] = rlam; }
 }
 
 // ---- operand with strided vectors (B, columns of a row-major matrix) ------------------------
