@@ -626,8 +626,19 @@ __global__ __launch_bounds__(1024) void scan_pair_kernel(const int32_t* t0, int6
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int64_t per = (nvec + 1023) / 1024;
   const int64_t v0 = tid * per, v1 = v0 + per < nvec ? v0 + per : nvec;
+  // (spans of up to sixteen vectors are held in registers: their loads are independent and
+  // all in flight at once)
+  constexpr int kHeld = 16;
+  int32_t held[kHeld];
   int64_t x = 0;
-  for (int64_t v = v0; v < v1; ++v) x += totals[v];
+  if (per <= kHeld) {
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i) held[i] = v0 + i < v1 ? totals[v0 + i] : 0;
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i) x += held[i];
+  } else {
+    for (int64_t v = v0; v < v1; ++v) x += totals[v];
+  }
   int64_t inc = x;
   for (int d = 1; d < 64; d <<= 1) {
     int64_t y = __shfl_up(inc, d, 64);
@@ -637,9 +648,17 @@ __global__ __launch_bounds__(1024) void scan_pair_kernel(const int32_t* t0, int6
   __syncthreads();
   int64_t run = inc - x;                              // exclusive prefix of this thread's span
   for (int i = 0; i < w; ++i) run += wave_sum[i];
-  for (int64_t v = v0; v < v1; ++v) {
-    ptr[v] = (int32_t)run;
-    run += totals[v];
+  if (per <= kHeld) {
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i) {
+      if (v0 + i < v1) ptr[v0 + i] = (int32_t)run;
+      run += held[i];
+    }
+  } else {
+    for (int64_t v = v0; v < v1; ++v) {
+      ptr[v] = (int32_t)run;
+      run += totals[v];
+    }
   }
   if (tid == 1023) {
     ptr[nvec] = (int32_t)run;

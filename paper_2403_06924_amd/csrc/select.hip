@@ -40,7 +40,8 @@ __global__ void reduce_means_pair_kernel(const double* __restrict__ part0, int64
   const double* part = second ? part1 : part0;
   const int64_t nparts = second ? nparts1 : nparts0, nvec = second ? n1 : n0;
   double s = 0.0;
-  for (int64_t p = 0; p < nparts; ++p) s += part[p * nvec + v];
+#pragma unroll 8
+  for (int64_t p = 0; p < nparts; ++p) s += part[p * nvec + v];   // fixed order: reproducible means
   float m = (float)(s / (second ? count1 : count0));
   (second ? mean1 : mean0)[v] = m;
   (second ? thresh1 : thresh0)[v] = (second ? theta1 : theta0) * m;
