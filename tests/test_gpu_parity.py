@@ -315,7 +315,7 @@ def test_ragged_shapes_all_strategies(srq, b, name, shape, strategy):
     check_against_oracle(srq, b, A, B, ta, tb, strategy=strategy)
 
 
-@pytest.mark.parametrize("shape", [(300, 200, 2048), (257, 129, 1531), (64, 96, 4100)])
+@pytest.mark.parametrize("shape", [(300, 200, 2048), (257, 129, 1531), (64, 96, 4100), (132, 260, 640)])
 @pytest.mark.parametrize("density", [1e-3, 2e-4])
 def test_very_sparse_operands_auto(srq, b, shape, density):
     """Well under one kept entry per 512 elements, host-synchronising mode: the compaction takes the
