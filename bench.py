@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3", help="C1..C5 (default C3: 8192^3 with outliers)")
     ap.add_argument("--density", type=float, default=None, help="target density of A' and B'")
-    ap.add_argument("--strategy", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--strategy", default="auto", choices=["auto", "valu", "mfma", "smfmac"])
     ap.add_argument("--dense-fallback", type=float, default=2.0, help="Algorithm 1's limit s (>1: off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
@@ -136,7 +136,8 @@ def main():
     del Qa, Qb
     torch.cuda.empty_cache()
 
-    strategy = {"auto": b.STRATEGY_AUTO, "valu": b.STRATEGY_CSR_VALU, "mfma": b.STRATEGY_CSR_MFMA}[args.strategy]
+    strategy = {"auto": b.STRATEGY_AUTO, "valu": b.STRATEGY_CSR_VALU, "mfma": b.STRATEGY_CSR_MFMA,
+                "smfmac": b.STRATEGY_CSR_SMFMAC}[args.strategy]
     stats = b.stats_tensor()
     Cd = torch.empty((M, N), dtype=torch.float32, device="cuda")
     max_density = min(1.0, density * 1.25 + 0.01)

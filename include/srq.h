@@ -63,7 +63,12 @@ typedef enum srq_round_t { SRQ_ROUND_NEAREST_EVEN = 0, SRQ_ROUND_TRUNC = 1 } srq
 typedef enum srq_strategy_t {
   SRQ_STRATEGY_AUTO = 0,        /* pick per term from the measured density (synchronises)   */
   SRQ_STRATEGY_CSR_VALU = 1,    /* row-wise CSR x dense on the vector ALUs                   */
-  SRQ_STRATEGY_CSR_MFMA = 2     /* CSR expanded to zero-filled INT8 tiles, matrix cores      */
+  SRQ_STRATEGY_CSR_MFMA = 2,    /* CSR expanded to zero-filled INT8 tiles, matrix cores      */
+  SRQ_STRATEGY_CSR_SMFMAC = 3   /* expansion split into a 2:4 operand for the sparse matrix-   */
+                                /* core instruction + a spill list on the vector ALUs (needs */
+                                /* M, N multiples of 256; otherwise runs as CSR_MFMA).  The   */
+                                /* spilled part of a term is added to C separately, so C is  */
+                                /* within rounding of, not bit-identical to, the other paths  */
 } srq_strategy_t;
 
 /* Granularity of the first-level scales in srq_compensated_gemm.  VECTOR is the method of
@@ -79,7 +84,7 @@ typedef struct srq_stats_t {
   int64_t nnz_a;        /* entries kept in A' (Algorithm 1, getSparsity)                    */
   int64_t nnz_b;        /* entries kept in B'                                               */
   int32_t path_a;       /* 0 = term skipped (theta = inf), 1 = CSR_VALU, 2 = CSR_MFMA,      */
-  int32_t path_b;       /* 3 = dense branch on the unreduced operand                        */
+  int32_t path_b;       /* 3 = dense branch on the unreduced operand, 4 = CSR_SMFMAC        */
 } srq_stats_t;
 
 /* Optional extra outputs of srq_compensated_gemm for stage-by-stage checks; any member may

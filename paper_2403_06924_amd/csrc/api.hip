@@ -21,6 +21,12 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // straight), 0.15 ms + 0.37 ms per percent for B' (columns of C, through LDS); the expanded
 // operand on the matrix cores takes 0.49-0.58 ms at any density.  The same crossovers (1.3-1.5 %
 // and 0.75 %) were measured at 2048^3 and 4096^3.
+// execution of a correction term as reported in srq_stats_t (0: term skipped)
+constexpr int kPathValu = 1, kPathMfma = 2, kPathDense = 3, kPath24 = 4;
+inline int strategy_path(srq_strategy_t s) {
+  return s == SRQ_STRATEGY_CSR_VALU ? kPathValu : s == SRQ_STRATEGY_CSR_SMFMAC ? kPath24 : kPathMfma;
+}
+
 constexpr double kAutoMfmaDensityA = 0.012;
 constexpr double kAutoMfmaDensityALongK = 0.008;
 constexpr double kAutoMfmaDensityB = 0.009;
@@ -49,10 +55,20 @@ struct Plan {
   int32_t *a_idx, *b_idx;
   int8_t *a_val, *b_val;
   int64_t cap_a, cap_b;
+  // 2:4 form of the reduced operands: kept codes, position nibbles, spill lists
+  int8_t *a24v, *b24v;
+  uint8_t *a24n, *b24n;
+  int32_t *sa_begin, *sa_end, *sb_begin, *sb_end, *sa_idx, *sb_idx;
+  int8_t *sa_val, *sb_val;
+  unsigned long long* sp_total;   // [2]
+  int64_t cap_sa, cap_sb;
   size_t fixed_bytes;
 };
 
 int64_t tiles(int64_t n, int t) { return (n + t - 1) / t; }
+
+// workspace per kept entry: index + value, and half an entry of spill list (2:4 split)
+constexpr double kBytesPerEntry = 7.5;
 
 // Leading dimension of the K-contiguous code matrices in the workspace: K rounded up to a
 // multiple of 128 with zeros in the padding, so that every row is 128-byte aligned and the
@@ -87,15 +103,23 @@ size_t plan_fixed(char* base, int64_t M, int64_t N, int64_t K, Plan* p) {
   p->nnz = c.take<int64_t>(2);
   p->mask_a = c.take<uint64_t>((size_t)M * mask_words(K));
   p->mask_b = c.take<uint64_t>((size_t)N * mask_words(K));
+  const size_t mk256 = (size_t)((M + 255) / 256 * 256) * Kc, nk256 = (size_t)((N + 255) / 256 * 256) * Kc;
+  p->a24v = c.take<int8_t>(mk256 / 2); p->a24n = c.take<uint8_t>(mk256 / 8);
+  p->b24v = c.take<int8_t>(nk256 / 2); p->b24n = c.take<uint8_t>(nk256 / 8);
+  p->sa_begin = c.take<int32_t>(M); p->sa_end = c.take<int32_t>(M);
+  p->sb_begin = c.take<int32_t>(N); p->sb_end = c.take<int32_t>(N);
+  p->sp_total = c.take<unsigned long long>(2);
   p->fixed_bytes = c.off;
   return c.off;
 }
 
 // Splits what is left of the workspace into the two compressed operands.
 bool plan_compressed(char* base, size_t bytes, int64_t M, int64_t N, int64_t K, Plan* p) {
-  if (bytes < p->fixed_bytes + 4 * kAlign) { p->cap_a = p->cap_b = 0; return false; }
-  size_t rest = bytes - p->fixed_bytes - 4 * kAlign;
-  double total = (double)(rest / 5);
+  if (bytes < p->fixed_bytes + 8 * kAlign) { p->cap_a = p->cap_b = p->cap_sa = p->cap_sb = 0; return false; }
+  size_t rest = bytes - p->fixed_bytes - 8 * kAlign;
+  // 5 bytes per kept entry, and room for half as many spilled entries of the 2:4 split (at most
+  // two of the four entries of a group spill)
+  double total = (double)rest / kBytesPerEntry;
   double fa = (M + N) > 0 ? (double)M / (double)(M + N) : 0.5;
   int64_t cap_a = (int64_t)(total * fa), cap_b = (int64_t)(total * (1.0 - fa));
   int64_t max_a = M * K, max_b = N * K;
@@ -106,12 +130,18 @@ bool plan_compressed(char* base, size_t bytes, int64_t M, int64_t N, int64_t K, 
   if (cap_b > lim) cap_b = lim;
   p->cap_a = cap_a;
   p->cap_b = cap_b;
+  p->cap_sa = (cap_a + 1) / 2;
+  p->cap_sb = (cap_b + 1) / 2;
   if (base) {
     Carver c{base, p->fixed_bytes};
     p->a_idx = c.take<int32_t>(cap_a);
     p->a_val = c.take<int8_t>(cap_a);
     p->b_idx = c.take<int32_t>(cap_b);
     p->b_val = c.take<int8_t>(cap_b);
+    p->sa_idx = c.take<int32_t>(p->cap_sa);
+    p->sa_val = c.take<int8_t>(p->cap_sa);
+    p->sb_idx = c.take<int32_t>(p->cap_sb);
+    p->sb_val = c.take<int8_t>(p->cap_sb);
   }
   return true;
 }
@@ -255,7 +285,7 @@ srq_status_t srq_workspace_bytes(int64_t M, int64_t N, int64_t K, double max_den
   size_t fixed = plan_fixed(nullptr, M, N, K, &p);
   // the capacity is shared out in proportion to the operand sizes, so size for the larger
   double entries = max_density * (double)K * (double)(M + N) + 1024.0;
-  size_t total = fixed + 4 * kAlign + (size_t)(entries * 5.0) + 64;
+  size_t total = fixed + 8 * kAlign + (size_t)(entries * kBytesPerEntry) + 64;
   size_t st = stage_bytes(M, N, K);
   *bytes = align_up(total > st ? total : st);
   return SRQ_STATUS_OK;
@@ -461,7 +491,7 @@ srq_status_t srq_spmm_accumulate(srq_handle_t h, srq_axis_t side, srq_strategy_t
   ep.alpha = 1.f;
   const int64_t cap = 2147483647LL;
   if (strategy == SRQ_STRATEGY_CSR_VALU) {
-    SRQ_HIP(h, launch_spmm_valu(side == SRQ_AXIS_ROW ? 0 : 1, nvec, nelem, K, ptr, idx, val, cap, Rq, ldr, ep, st));
+    SRQ_HIP(h, launch_spmm_valu(side == SRQ_AXIS_ROW ? 0 : 1, nvec, nelem, K, ptr, nullptr, idx, val, cap, Rq, ldr, ep, st));
   } else {
     int8_t* dense = reinterpret_cast<int8_t*>(h->ws);
     int64_t ldd = (K + 15) / 16 * 16;
@@ -486,7 +516,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   if (s) return s;
   if (M < 0 || N < 0 || K < 0) return SRQ_STATUS_INVALID_ARG;
   if (round != SRQ_ROUND_NEAREST_EVEN && round != SRQ_ROUND_TRUNC) return SRQ_STATUS_INVALID_ARG;
-  if (strategy != SRQ_STRATEGY_AUTO && strategy != SRQ_STRATEGY_CSR_VALU && strategy != SRQ_STRATEGY_CSR_MFMA)
+  if (strategy != SRQ_STRATEGY_AUTO && strategy != SRQ_STRATEGY_CSR_VALU && strategy != SRQ_STRATEGY_CSR_MFMA &&
+      strategy != SRQ_STRATEGY_CSR_SMFMAC)
     return SRQ_STATUS_INVALID_ARG;
   if (isnan(theta_a) || isnan(theta_b) || theta_a < 0.f || theta_b < 0.f) return SRQ_STATUS_INVALID_ARG;
   if (isnan(dense_fallback_density) || isnan(alpha) || isnan(beta)) return SRQ_STATUS_INVALID_ARG;
@@ -533,7 +564,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   const bool fastA = K > 0 && !global_scale && rows_fused_ok(A, K, lda, p.A_int, Kc, p.RA_int, Kc);
   const bool fastB = K > 0 && !global_scale && cols_pass_ok(B, N, ldb);
   bool ra_vm_done = false, ra_em_done = false, rb_vm_done = false, rb_em_done = false;
-  bool rb_in_select = false, rb_want_em = false;   // residual codes of B left to the selection pass
+  bool rb_in_select = false, rb_want_em = false, rb_want_vm = false;   // residual codes of B left to the selection pass
   // lines 1: Quant.  amax per vector -> scale, lambda -> codes (and max |residual| per vector)
   {
   StageTimer tm(h, st, SRQ_STAGE_QUANTIZE);
@@ -551,7 +582,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // residual scales are produced here and A's selection pass writes the k-major codes
     const bool skip_ra_vm = comp && term_b && dense_fallback_density > 1.f &&
                             (strategy == SRQ_STRATEGY_CSR_VALU ||
-                             (strategy == SRQ_STRATEGY_AUTO && h->last_path_b == SRQ_STRATEGY_CSR_VALU));
+                             (strategy == SRQ_STRATEGY_AUTO && h->last_path_b == kPathValu));
     SRQ_HIP(h, launch_rows_fused(A, M, K, lda, qmax, trunc, p.A_int, Kc, p.s_a, p.lam_a,
                                  (comp && !skip_ra_vm) ? p.RA_int : nullptr, Kc, comp ? p.s_ra : nullptr,
                                  comp ? p.lam_ra : nullptr, st));
@@ -582,17 +613,19 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       // (or, with SRQ_STRATEGY_AUTO, if the previous call on this handle ended up there: repeated
       // calls at a similar density then write the layout they need here and not in a second pass;
       // a wrong guess only costs that second pass)
-      const bool want_em = term_a && dense_fallback_density > 1.f &&
-                           (strategy == SRQ_STRATEGY_CSR_VALU ||
-                            (strategy == SRQ_STRATEGY_AUTO && h->last_path_a == SRQ_STRATEGY_CSR_VALU));
+      // (the 2:4 path reads both: K-contiguous codes on the matrix cores, k-major ones for its spill)
+      const int expect_a = strategy == SRQ_STRATEGY_AUTO ? h->last_path_a : strategy_path(strategy);
+      const bool want_em = term_a && dense_fallback_density > 1.f && (expect_a == kPathValu || expect_a == kPath24);
+      const bool want_vm = !want_em || expect_a == kPath24;
       // when B's selection pass will run it writes these codes too (one read of B less)
       rb_in_select = term_b;
       rb_want_em = want_em;
+      rb_want_vm = want_vm;
       if (!rb_in_select)
         SRQ_HIP(h, launch_cols_resid_from_amax(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.ramax_b, p.s_rb,
-                                               p.lam_rb, want_em ? nullptr : p.RB_int, Kc,
+                                               p.lam_rb, want_vm ? p.RB_int : nullptr, Kc,
                                                want_em ? p.RB_em : nullptr, N, st));
-      rb_vm_done = !want_em;
+      rb_vm_done = want_vm;
       rb_em_done = want_em;
     }
   } else {
@@ -639,9 +672,9 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       // if term 2 is expected on the vector ALUs (fixed by the caller, or where SRQ_STRATEGY_AUTO
       // ended up in the previous call), A's selection pass also writes the k-major residual
       // codes that execution reads: one read of A less
+      const int expect_b = strategy == SRQ_STRATEGY_AUTO ? h->last_path_b : strategy_path(strategy);
       const bool want_ra_em = term_b && dense_fallback_density > 1.f &&
-                              (strategy == SRQ_STRATEGY_CSR_VALU ||
-                               (strategy == SRQ_STRATEGY_AUTO && h->last_path_b == SRQ_STRATEGY_CSR_VALU)) &&
+                              (expect_b == kPathValu || expect_b == kPath24) &&
                               rows_mask_resid_em_ok(A, M, K, lda, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M, p.t_a);
       if (want_ra_em) {
         SRQ_HIP(h, launch_rows_mask_resid_em(A, M, K, lda, qmax, trunc, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M,
@@ -656,7 +689,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
         // (tot_b was cleared in the quantize stage)
         if (rb_in_select)
           SRQ_HIP(h, launch_cols_mask_resid(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.ramax_b, p.s_rb, p.lam_rb,
-                                            rb_want_em ? nullptr : p.RB_int, Kc, rb_want_em ? p.RB_em : nullptr,
+                                            rb_want_vm ? p.RB_int : nullptr, Kc, rb_want_em ? p.RB_em : nullptr,
                                             N, p.t_b, p.mask_b, p.tot_b, st));
         else
           SRQ_HIP(h, launch_cols_mask(B, K, N, ldb, p.t_b, p.mask_b, p.tot_b, st));
@@ -680,7 +713,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       auto pick = [&](double d, double crossover) {
         if (d >= (double)dense_fallback_density) return 3;
         if (strategy == SRQ_STRATEGY_AUTO) return d >= crossover ? 2 : 1;
-        return (int)strategy;
+        return strategy_path(strategy);
       };
       // (for K > 8192 the K x 512-byte slab of codes an XCD gathers from outgrows its L2 and the
       // vector-ALU kernel loses earlier: measured crossover 0.8 % at 16384^3)
@@ -694,9 +727,19 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
         return SRQ_STATUS_CAPACITY;
       }
     } else {
-      if (term_a) path_a = (int)strategy;
-      if (term_b) path_b = (int)strategy;
+      if (term_a) path_a = strategy_path(strategy);
+      if (term_b) path_b = strategy_path(strategy);
     }
+    // the 2:4 kernel needs whole 256 x 256 tiles of C and cannot write the raw sums the debug
+    // block asks for: such a term takes the plain matrix-core path
+    if (path_a == kPath24 &&
+        (dbg || !gemm_sparse24_ok(M, N, Kc, p.a24v, p.a24n, p.RB_int, Kc, false, ep)))
+      path_a = kPathMfma;
+    if (path_b == kPath24 &&
+        (dbg || !gemm_sparse24_ok(N, M, Kc, p.b24v, p.b24n, p.RA_int, Kc, true, ep)))
+      path_b = kPathMfma;
+    if (path_a == kPath24 || path_b == kPath24)
+      SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.sp_total), 4, 0, st));   // spill counters
     // compaction to CSR of A' / CSC of B'; a term that will run on the matrix cores also gets
     // its operand expanded to zero-filled dense codes in the same pass
     // (the dense branch multiplies the unreduced codes: its operand is counted, not compacted)
@@ -704,7 +747,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       im.a_ptr = p.a_ptr; im.capacity_a = p.cap_a;
       if (path_a != 3) {
         SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, Kc, p.a_ptr, p.a_idx, p.a_val, p.cap_a,
-                                       path_a == 2 ? p.Ad : nullptr, Kc, known_a, st));
+                                       (path_a == kPathMfma || path_a == kPath24) ? p.Ad : nullptr, Kc, known_a, st));
         im.a_idx = p.a_idx; im.a_val = p.a_val;
       }
     }
@@ -713,18 +756,20 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     } else if (term_b) {
       if (fastB) {
         SRQ_HIP(h, launch_scatter_mask(p.mask_b, N, K, p.B_int, Kc, p.b_ptr, p.b_idx, p.b_val, p.cap_b,
-                                       path_b == 2 ? p.Bd : nullptr, Kc, known_b, st));
+                                       (path_b == kPathMfma || path_b == kPath24) ? p.Bd : nullptr, Kc, known_b, st));
       } else {
         SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
                                          p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));
-        if (path_b == 2) SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, Kc, st));
+        if (path_b == kPathMfma || path_b == kPath24)
+          SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, Kc, st));
       }
       im.b_ptr = p.b_ptr; im.b_idx = p.b_idx; im.b_val = p.b_val; im.capacity_b = p.cap_b;
     }
     }
     // lines 4-6: residual matrices and their codes, in the layouts the chosen paths read
     // (RA feeds term 2, RB feeds term 1)
-    bool ra_vm = path_b >= 2, ra_em = path_b == 1, rb_vm = path_a >= 2, rb_em = path_a == 1;
+    bool ra_vm = path_b >= 2, ra_em = path_b == kPathValu || path_b == kPath24;
+    bool rb_vm = path_a >= 2, rb_em = path_a == kPathValu || path_a == kPath24;
     {
     StageTimer tm(h, st, SRQ_STAGE_RESIDUAL);
     // whatever the quantize stage has not already produced
@@ -759,13 +804,26 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     e1.final_scale = scale_needed && path_b == 0;
     if (path_a == 1) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
-      SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.a_ptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, e1, st));
+      SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.a_ptr, nullptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, e1, st));
     } else if (path_a == 2) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, e1, st));
     } else if (path_a == 3) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.A_int, Kc, p.RB_int, Kc, e1, st));
+    } else if (path_a == kPath24) {
+      // 2:4 part on the sparse matrix cores, then the spilled entries on the vector ALUs
+      {
+        StageTimer tm(h, st, SRQ_STAGE_TERM1_PREP);
+        SRQ_HIP(h, launch_compress24(p.Ad, Kc, M, Kc, p.a24v, p.a24n, p.sa_begin, p.sa_end,
+                                     p.sa_idx, p.sa_val, p.cap_sa, p.sp_total, st));
+      }
+      StageTimer tm(h, st, SRQ_STAGE_TERM1);
+      GemmEpilogue em = e1;
+      em.final_scale = 0;
+      SRQ_HIP(h, launch_gemm_i8_sparse24(M, N, Kc, p.a24v, p.a24n, p.RB_int, Kc, false, em, st));
+      SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.sa_begin, p.sa_end, p.sa_idx, p.sa_val, p.cap_sa, p.RB_em, N, e1,
+                                  st));
     }
     GemmEpilogue e2 = e1;
     e2.s_row = p.s_ra; e2.s_col = p.s_b;
@@ -773,13 +831,25 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     e2.final_scale = scale_needed;
     if (path_b == 1) {
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
-      SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.b_ptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, e2, st));
+      SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.b_ptr, nullptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, e2, st));
     } else if (path_b == 2) {
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
       SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.RA_int, Kc, p.Bd, Kc, e2, st));
     } else if (path_b == 3) {
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
       SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.RA_int, Kc, p.B_int, Kc, e2, st));
+    } else if (path_b == kPath24) {
+      {
+        StageTimer tm(h, st, SRQ_STAGE_TERM2_PREP);
+        SRQ_HIP(h, launch_compress24(p.Bd, Kc, N, Kc, p.b24v, p.b24n, p.sb_begin, p.sb_end,
+                                     p.sb_idx, p.sb_val, p.cap_sb, p.sp_total + 1, st));
+      }
+      StageTimer tm(h, st, SRQ_STAGE_TERM2);
+      GemmEpilogue em = e2;
+      em.final_scale = 0;
+      SRQ_HIP(h, launch_gemm_i8_sparse24(N, M, Kc, p.b24v, p.b24n, p.RA_int, Kc, true, em, st));
+      SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.sb_begin, p.sb_end, p.sb_idx, p.sb_val, p.cap_sb, p.RA_em, M, e2,
+                                  st));
     }
     if (scale_needed && path_a == 0 && path_b == 0) {
       GemmEpilogue e3 = ep;

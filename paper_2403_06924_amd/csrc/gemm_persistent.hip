@@ -16,6 +16,7 @@
 //    tile is multiplied.  A one-tile-per-workgroup launch pays launch, prologue latency and
 //    drain once per tile - four times per CU at 8192^3, since only one workgroup fits a CU.
 #include "srq_internal.h"
+#include "gemm_tiles.h"
 
 namespace srq {
 namespace {
@@ -30,27 +31,6 @@ constexpr int TM = 4, TN = 4;                       // 32x32 MFMA tiles per wave
 constexpr int kLdsScales = 2 * kStage;              // float[BM + BN]
 constexpr int kLdsRed = kLdsScales + (BM + BN) * 4; // double[2][256]
 constexpr int kLdsBytes = kLdsRed + 2 * 256 * 8;
-
-// tile coordinates of the vb-th tile in launch order: XCD-contiguous bands, groups of 8 rows
-__device__ __forceinline__ void tile_of(int64_t vb, int64_t tiles_m, int64_t tiles_n, int64_t& tm, int64_t& tn) {
-  const int64_t total = tiles_m * tiles_n, per = total / 8;
-  int64_t bid = vb;
-  if (per > 0 && bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
-  const int64_t g = 8;
-  int64_t grp = bid / (g * tiles_n), first = grp * g;
-  int64_t rows_in = tiles_m - first < g ? tiles_m - first : g;
-  int64_t in = bid - grp * g * tiles_n;
-  tm = first + in % rows_in;
-  tn = in / rows_in;
-}
-
-// One wave-wide 16-byte-per-lane load from global memory into LDS: lane l's bytes land at
-// lds_base + 16*l.  Issued as inline assembly so that its completion is waited for explicitly
-// (wait_loads) right before the barrier that publishes the tile, not before every LDS read.
-__device__ __forceinline__ void load_to_lds(const int8_t* gptr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
-}
-__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
 
 template <int MODE, bool SUMS, bool SCALE>
 __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int64_t N, int64_t K,

@@ -17,13 +17,14 @@ constexpr int kBlockElems = 64 * kLaneElems;  // one wave per block
 template <int SIDE>
 __global__ __launch_bounds__(64) void spmm_valu_kernel(int64_t nvec, int64_t nelem,
                                                        const int32_t* __restrict__ ptr,
+                                                       const int32_t* __restrict__ ptr_end,
                                                        const int32_t* __restrict__ idx,
                                                        const int8_t* __restrict__ val, int64_t capacity,
                                                        const int8_t* __restrict__ R, int64_t ldr,
                                                        GemmEpilogue ep) {
   const int64_t v = blockIdx.y;
   const int64_t e0 = (int64_t)blockIdx.x * kBlockElems + threadIdx.x * kLaneElems;
-  int64_t p0 = ptr[v], p1 = ptr[v + 1];
+  int64_t p0 = ptr[v], p1 = ptr_end[v];
   if (p1 > capacity) p1 = capacity;
   int acc[kLaneElems] = {0, 0, 0, 0};
   const bool full = e0 + kLaneElems <= nelem;
@@ -110,6 +111,7 @@ __device__ __forceinline__ int word_of(word4_t x, int i) { return i == 0 ? x.x :
 template <int SIDE, int LE>
 __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t nelem,
                                                         const int32_t* __restrict__ ptr,
+                                                        const int32_t* __restrict__ ptr_end,
                                                         const int32_t* __restrict__ idx,
                                                         const int8_t* __restrict__ val, int64_t capacity,
                                                         const int8_t* __restrict__ R, int64_t ldr,
@@ -128,13 +130,14 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
   const bool lane_in = e0 < nelem;                 // nelem is a multiple of LE
   const uint32_t eoff = lane_in ? (uint32_t)e0 : 0u;   // lanes past the end gather from column 0 and store nothing
 
-  // the nine row pointers of the wave's eight vectors, one per lane
+  // first and one-past-last pair of the wave's eight vectors, one vector per lane (for plain
+  // CSR the end of a vector is the start of the next: ptr_end = ptr + 1)
   const int64_t v0 = (int64_t)vb * kVecPerBlock + w * kVecPerWave;
-  int pl = 0;
-  if (lane <= kVecPerWave) {
-    const int64_t vv = v0 + lane < nvec ? v0 + lane : nvec;
-    const int64_t pp = ptr[vv];
+  int pl = 0, pe = 0;
+  if (lane < kVecPerWave && v0 + lane < nvec) {
+    const int64_t pp = ptr[v0 + lane], qq = ptr_end[v0 + lane];
     pl = (int)(pp < capacity ? pp : capacity);
+    pe = (int)(qq < capacity ? qq : capacity);
   }
   typedef typename LaneWords<LE>::type words_t;
   // raw buffer over the code matrix; the caller guarantees K * ldr < 2^32
@@ -147,7 +150,7 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
 #pragma unroll
     for (int t = 0; t < LE; ++t) acc[t] = 0;
     if (v < nvec) {
-      const int p0 = __builtin_amdgcn_readlane(pl, q), p1 = __builtin_amdgcn_readlane(pl, q + 1);
+      const int p0 = __builtin_amdgcn_readlane(pl, q), p1 = __builtin_amdgcn_readlane(pe, q);
       for (int pb = p0; pb < p1; pb += 64) {
         const int cnt = p1 - pb < 64 ? p1 - pb : 64;
         uint32_t ro = 0;                             // padding pairs: value 0 times row 0
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
       for (int t = 0; t < LE; ++t) dst[t] = acc[t];
     } else if (v < nvec && lane_in &&
                (ep.final_scale || ep.D_int ||
-                __builtin_amdgcn_readlane(pl, q) != __builtin_amdgcn_readlane(pl, q + 1))) {
+                __builtin_amdgcn_readlane(pl, q) < __builtin_amdgcn_readlane(pe, q))) {
       // (a row without kept entries leaves C as it is unless this pass also applies alpha / beta)
       const float sr = ep.s_row[v];
       float* c = ep.C + v * ep.ldc + e0;
@@ -280,7 +283,7 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
 }
 
 template <int SIDE, int LE>
-hipError_t launch_tile(int64_t nvec, int64_t nelem, const int32_t* ptr, const int32_t* idx,
+hipError_t launch_tile(int64_t nvec, int64_t nelem, const int32_t* ptr, const int32_t* ptr_end, const int32_t* idx,
                        const int8_t* val, int64_t capacity, const int8_t* R, int64_t ldr,
                        const GemmEpilogue& ep, hipStream_t st) {
   constexpr int E = 64 * LE;
@@ -293,7 +296,7 @@ hipError_t launch_tile(int64_t nvec, int64_t nelem, const int32_t* ptr, const in
                     (!ep.Cin || ((reinterpret_cast<uintptr_t>(ep.Cin) & 15) == 0 && ep.ldcin % 4 == 0));
   const size_t lds = SIDE == 1 ? (size_t)kVecPerBlock * (E + 1) * sizeof(int) : 0;
   hipLaunchKernelGGL((spmm_tile_kernel<SIDE, LE>), dim3((unsigned)blocks), dim3(256), lds, st, nvec, nelem,
-                     ptr, idx, val, capacity, R, ldr, ep, (int)nvb, (int)nch, cvec);
+                     ptr, ptr_end, idx, val, capacity, R, ldr, ep, (int)nvb, (int)nch, cvec);
   return hipGetLastError();
 }
 
@@ -308,18 +311,20 @@ bool tile_ok(int64_t nvec, int64_t nelem, int64_t K, const int8_t* R, int64_t ld
 }  // namespace
 
 hipError_t launch_spmm_valu(int side, int64_t nvec, int64_t nelem, int64_t K, const int32_t* ptr,
-                            const int32_t* idx, const int8_t* val, int64_t capacity, const int8_t* R,
-                            int64_t ldr, const GemmEpilogue& ep, hipStream_t st) {
+                            const int32_t* ptr_end, const int32_t* idx, const int8_t* val, int64_t capacity,
+                            const int8_t* R, int64_t ldr, const GemmEpilogue& ep, hipStream_t st) {
   if (nvec <= 0 || nelem <= 0) return hipSuccess;
+  if (!ptr_end) ptr_end = ptr + 1;                 // plain CSR / CSC
   if (side == 0 && tile_ok(nvec, nelem, K, R, ldr, 8))
-    return launch_tile<0, 8>(nvec, nelem, ptr, idx, val, capacity, R, ldr, ep, st);
+    return launch_tile<0, 8>(nvec, nelem, ptr, ptr_end, idx, val, capacity, R, ldr, ep, st);
   if (side == 1 && tile_ok(nvec, nelem, K, R, ldr, 4))
-    return launch_tile<1, 4>(nvec, nelem, ptr, idx, val, capacity, R, ldr, ep, st);
+    return launch_tile<1, 4>(nvec, nelem, ptr, ptr_end, idx, val, capacity, R, ldr, ep, st);
   const int64_t kMaxY = 65535;
   for (int64_t v0 = 0; v0 < nvec; v0 += kMaxY) {   // gridDim.y is limited to 65535
     int64_t nv = nvec - v0 < kMaxY ? nvec - v0 : kMaxY;
     GemmEpilogue e2 = ep;
     const int32_t* p2 = ptr + v0;
+    const int32_t* q2 = ptr_end + v0;
     // shift the output window so that blockIdx.y = 0 is vector v0
     if (side == 0) {
       e2.C = ep.C + v0 * ep.ldc;
@@ -334,10 +339,10 @@ hipError_t launch_spmm_valu(int side, int64_t nvec, int64_t nelem, int64_t K, co
     }
     dim3 grid((unsigned)((nelem + kBlockElems - 1) / kBlockElems), (unsigned)nv);
     if (side == 0)
-      hipLaunchKernelGGL(spmm_valu_kernel<0>, grid, dim3(64), 0, st, nv, nelem, p2, idx, val, capacity, R,
+      hipLaunchKernelGGL(spmm_valu_kernel<0>, grid, dim3(64), 0, st, nv, nelem, p2, q2, idx, val, capacity, R,
                          ldr, e2);
     else
-      hipLaunchKernelGGL(spmm_valu_kernel<1>, grid, dim3(64), 0, st, nv, nelem, p2, idx, val, capacity, R,
+      hipLaunchKernelGGL(spmm_valu_kernel<1>, grid, dim3(64), 0, st, nv, nelem, p2, q2, idx, val, capacity, R,
                          ldr, e2);
   }
   return hipGetLastError();

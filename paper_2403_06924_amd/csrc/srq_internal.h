@@ -174,10 +174,25 @@ hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8
 hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* val, int64_t nvec,
                           int64_t veclen, int64_t capacity, int8_t* dense, int64_t ld, hipStream_t st);
 
-// VALU SpMM.  out[v, e] = sum_p val[p] * R[idx[p]*ldr + e];  side 0: C[v, e], side 1: C[e, v]
+// VALU SpMM.  out[v, e] = sum_p val[p] * R[idx[p]*ldr + e];  side 0: C[v, e], side 1: C[e, v].
+// Vector v owns the pairs [ptr[v], ptr_end[v]); ptr_end == null means plain CSR (ptr + 1).
 hipError_t launch_spmm_valu(int side, int64_t nvec, int64_t nelem, int64_t K, const int32_t* ptr,
-                            const int32_t* idx, const int8_t* val, int64_t capacity, const int8_t* R,
-                            int64_t ldr, const GemmEpilogue& ep, hipStream_t st);
+                            const int32_t* ptr_end, const int32_t* idx, const int8_t* val, int64_t capacity,
+                            const int8_t* R, int64_t ldr, const GemmEpilogue& ep, hipStream_t st);
+
+// ---- 2:4-structured execution (sparse24.hip, gemm_sparse24.hip)
+// split of a zero-filled expansion into 2:4 codes + position nibbles + a spill list
+// (vals / nib: K-tile-major per block of 256 vectors, (nvec rounded up to 256) * kc / 2 resp. / 8 bytes)
+hipError_t launch_compress24(const int8_t* dense, int64_t ldd, int64_t nvec, int64_t kc, int8_t* vals,
+                             uint8_t* nib, int32_t* sp_begin, int32_t* sp_end, int32_t* sp_idx,
+                             int8_t* sp_val, int64_t sp_capacity, unsigned long long* sp_total, hipStream_t st);
+// C += dequant(sparse . dense^T) (trans: C += dequant((sparse . dense^T)^T)); Mv, Nv vectors of the
+// sparse / dense operand
+bool gemm_sparse24_ok(int64_t Mv, int64_t Nv, int64_t K, const int8_t* Av, const uint8_t* An, const int8_t* Qb,
+                      int64_t ldb, bool trans, const GemmEpilogue& ep);
+hipError_t launch_gemm_i8_sparse24(int64_t Mv, int64_t Nv, int64_t K, const int8_t* Av, const uint8_t* An,
+                                   const int8_t* Qb, int64_t ldb, bool trans, const GemmEpilogue& ep,
+                                   hipStream_t st);
 
 hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b,
                         srq_stats_t* out, hipStream_t st);

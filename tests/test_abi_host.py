@@ -114,6 +114,7 @@ def test_compensated_gemm_validation(dry):
     assert _cg(dry, ta=-0.5) == b.INVALID_ARG
     assert _cg(dry, ta=float("nan")) == b.INVALID_ARG
     assert _cg(dry, strat=7) == b.INVALID_ARG
+    assert _cg(dry, strat=b.STRATEGY_CSR_SMFMAC) == b.NO_DEVICE
     assert _cg(dry, beta=1.0) == b.INVALID_ARG                  # beta needs Cin
     assert _cg(dry, beta=1.0, Cin=FAKE, ldcin=64) == b.NO_DEVICE
     assert _cg(dry, ta=float("inf"), tb=float("inf")) == b.NO_DEVICE
@@ -152,6 +153,7 @@ def test_staged_entry_points_validation(dry):
                                               FAKE, FAKE, None, 64, None)
     assert sp() == b.NO_DEVICE
     assert sp(strat=b.STRATEGY_AUTO) == b.INVALID_ARG
+    assert sp(strat=b.STRATEGY_CSR_SMFMAC) == b.INVALID_ARG   # whole-path call only
     assert sp(side=3) == b.INVALID_ARG
     assert sp(ptr=None) == b.INVALID_ARG
     assert sp(ldr=8) == b.INVALID_ARG

@@ -174,6 +174,27 @@ def test_c3_headline_sampled(srq, b):
     assert st["path_a"] in (1, 2) and st["path_b"] in (1, 2)
 
 
+def test_c3_structured_2to4_matches_matrix_core_path(srq, b):
+    """Full size, the launch configuration `bench.py --strategy smfmac` times: the 2:4 split + spill
+    execution of both terms against the plain matrix-core execution (which the test above checks
+    against the oracle).  The spilled part of a term is rounded into C separately, so the two agree
+    to rounding, not bit for bit."""
+    A, B = wl.make_inputs("C3")
+    Ad, Bd = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    ta, tb = gpu_thetas(srq, b, Ad, Bd, 0.05)
+    stats = b.stats_tensor()
+    C24, _, _ = srq.compensated_gemm(Ad, Bd, ta, tb, strategy=b.STRATEGY_CSR_SMFMAC, stats=stats, max_density=0.08)
+    torch.cuda.synchronize()
+    st = b.read_stats(stats)
+    assert st["path_a"] == 4 and st["path_b"] == 4
+    C24 = C24.clone()
+    C2, _, _ = srq.compensated_gemm(Ad, Bd, ta, tb, strategy=b.STRATEGY_CSR_MFMA, max_density=0.08)
+    torch.cuda.synchronize()
+    diff = (C24.double() - C2.double()).norm() / C2.double().norm()
+    assert float(diff) <= 1e-6
+    assert float((C24 == C2).float().mean()) > 0.5      # rows and columns without spilled entries agree exactly
+
+
 def test_c4_rectangular_sampled(srq, b):
     sampled_check(srq, b, "C4", 0.02, 128, seed=12)
 

@@ -344,6 +344,45 @@ def test_auto_repeated_calls_reuse_the_previous_choice(srq, b):
         assert st["path_a"] == st["path_b"] == (1 if density < 0.005 else 2)
 
 
+@pytest.mark.parametrize("shape", [(256, 256, 256), (512, 768, 384), (768, 512, 200), (256, 512, 1000)])
+@pytest.mark.parametrize("density", [0.05, 0.3])
+def test_structured_2to4_execution(srq, b, shape, density):
+    """SRQ_STRATEGY_CSR_SMFMAC: the reduced operand is split into a 2:4 operand for the sparse
+    matrix-core instruction and a spill list (third and fourth non-zero of a group of four k) for
+    the vector ALUs.  Selection and compressed arrays are the same as on every path (bit-exact);
+    the spilled part of a term is added to C by a second kernel, so C is compared to the
+    spec tolerance and, much tighter, to the plain matrix-core execution."""
+    M, N, K = shape
+    A, B = wl.make_inputs("C2", M, N, K)
+    plain = o.quantized_product(A, B)
+    drow, dcol = o.abs_means(plain.D_F)
+    ta = wl.theta_for_density(A, drow, "row", density)
+    tb = wl.theta_for_density(B, dcol, "col", density)
+    stats = b.stats_tensor()
+    C24, _, _ = srq.compensated_gemm(dev(A), dev(B), ta, tb, strategy=b.STRATEGY_CSR_SMFMAC, stats=stats)
+    torch.cuda.synchronize()
+    st = b.read_stats(stats)
+    im = srq.intermediates(M, N, K)
+    t_a, t_b = host(im["t_a"]), host(im["t_b"])
+    a_ptr, a_idx, a_val = host(im["a_ptr"]), host(im["a_idx"]), host(im["a_val"])
+    b_ptr, b_idx, b_val = host(im["b_ptr"]), host(im["b_idx"]), host(im["b_val"])
+    C24 = host(C24)
+    ref = o.compensated_gemm(A, B, ta, tb, thresh_a=t_a, thresh_b=t_b)
+    assert st["path_a"] == 4 and st["path_b"] == 4
+    assert st["nnz_a"] == ref.csr_a.nnz and st["nnz_b"] == ref.csc_b.nnz
+    assert (a_ptr == ref.csr_a.ptr).all() and (a_idx == ref.csr_a.idx).all() and (a_val == ref.csr_a.val).all()
+    assert (b_ptr == ref.csc_b.ptr).all() and (b_idx == ref.csc_b.idx).all() and (b_val == ref.csc_b.val).all()
+    assert rel_fro(ref.C, C24) <= REL_TOL
+    C2, _, _ = srq.compensated_gemm(dev(A), dev(B), ta, tb, strategy=b.STRATEGY_CSR_MFMA)
+    assert rel_fro(host(C2), C24) <= 1e-6
+    # with alpha and beta the scaling is applied once, after the last spill pass
+    Cin = np.random.default_rng(5).standard_normal((M, N)).astype(np.float32)
+    Cab, _, _ = srq.compensated_gemm(dev(A), dev(B), ta, tb, strategy=b.STRATEGY_CSR_SMFMAC, alpha=0.5, beta=-1.5,
+                                     C_in=dev(Cin))
+    refab = o.compensated_gemm(A, B, ta, tb, thresh_a=t_a, thresh_b=t_b, alpha=0.5, beta=-1.5, C_in=Cin)
+    assert rel_fro(refab.C, host(Cab)) <= REL_TOL
+
+
 def test_bounds_theta_inf_and_zero(srq, b):
     A, B = wl.make_inputs("C2", 200, 136, 300)
     inf = float("inf")
