@@ -215,7 +215,8 @@ srq_status_t srq_gemm_i8(srq_handle_t handle, int64_t M, int64_t N, int64_t K, c
  *   side = SRQ_AXIS_COL: DR = RA.B', (ptr,idx,val) = CSC of B' (N vectors over K), Rq = RA codes.
  * Rq layout: CSR_VALU wants the residual codes k-major (RB element-major K x N, ld >= N;
  * RA element-major K x M, ld >= M); CSR_MFMA wants them K-contiguous (RB vector-major
- * N x K; RA vector-major M x K; ld >= K).  SRQ_STRATEGY_AUTO is not accepted here.
+ * N x K; RA vector-major M x K; ld >= K).  SRQ_STRATEGY_AUTO and SRQ_STRATEGY_CSR_SMFMAC
+ * (which needs both layouts) are not accepted here.
  * s_row[M] / s_col[N] are the scales paired with rows / columns of C for this term.
  * DR_int (ld = ldc) may be NULL. */
 srq_status_t srq_spmm_accumulate(srq_handle_t handle, srq_axis_t side, srq_strategy_t strategy, int64_t M,
@@ -239,7 +240,8 @@ srq_status_t srq_spmm_accumulate(srq_handle_t handle, srq_axis_t side, srq_strat
  *   dbg                host pointer to a struct of device buffers, may be NULL.
  * An operand that is reduced (finite theta) must have fewer than 2^31 elements (INT32 row
  * pointers): SRQ_STATUS_UNSUPPORTED otherwise.
- * With a fixed strategy (CSR_VALU or CSR_MFMA) and dense_fallback_density > 1 the call only
+ * With dbg != NULL a CSR_SMFMAC term runs as CSR_MFMA (the 2:4 kernel has no raw-sum output).
+ * With a fixed strategy (CSR_VALU, CSR_MFMA or CSR_SMFMAC) and dense_fallback_density > 1 the call only
  * enqueues kernels on `stream`: no allocation, no host read-back, no memset node, so it may be
  * recorded into a HIP graph by a capturing caller (the workspace must be attached before).
  * Returns SRQ_STATUS_CAPACITY (after the first product and the selection ran: C then holds the
