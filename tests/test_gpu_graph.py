@@ -21,11 +21,11 @@ def srq():
     h.close()
 
 
-@pytest.mark.parametrize("strategy_name", ["mfma", "valu"])
+@pytest.mark.parametrize("strategy_name", ["mfma", "valu", "smfmac"])
 @pytest.mark.parametrize("shape", [(256, 256, 256), (1024, 768, 512)])
 def test_fixed_strategy_call_replays_from_a_graph(srq, strategy_name, shape):
     from paper_2403_06924_amd import binding as b
-    strategy = b.STRATEGY_CSR_MFMA if strategy_name == "mfma" else b.STRATEGY_CSR_VALU
+    strategy = {"mfma": b.STRATEGY_CSR_MFMA, "valu": b.STRATEGY_CSR_VALU, "smfmac": b.STRATEGY_CSR_SMFMAC}[strategy_name]
     M, N, K = shape
     rng = np.random.default_rng(M + N + K)
     def draw():
