@@ -802,7 +802,20 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     e1.s_row = p.s_a; e1.s_col = p.s_rb;
     e1.D_int = dbg ? dbg->DR1_int : nullptr;
     e1.final_scale = scale_needed && path_b == 0;
-    if (path_a == 1) {
+    // both terms on the dense matrix-core kernel: one launch, the two products of a tile back to
+    // back (the tile of C is still cached when the second product adds to it)
+    const int8_t* t1a = path_a == kPathMfma ? p.Ad : p.A_int;
+    const int8_t* t2b = path_b == kPathMfma ? p.Bd : p.B_int;
+    const bool pair = (path_a == kPathMfma || path_a == kPathDense) && (path_b == kPathMfma || path_b == kPathDense) &&
+                      !dbg && gemm_persistent_ok(M, N, Kc, t1a, Kc, p.RB_int, Kc, e1) &&
+                      gemm_persistent_ok(M, N, Kc, p.RA_int, Kc, t2b, Kc, e1);
+    if (pair) {
+      StageTimer tm(h, st, SRQ_STAGE_TERM1);
+      GemmEpilogue e12 = e1;
+      e12.final_scale = scale_needed;
+      const GemmSecond sec = {p.RA_int, t2b, Kc, Kc, p.s_ra, p.s_b};
+      SRQ_HIP(h, launch_gemm_i8_persistent(M, N, Kc, t1a, Kc, p.RB_int, Kc, e12, st, &sec));
+    } else if (path_a == 1) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.a_ptr, nullptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, e1, st));
     } else if (path_a == 2) {
@@ -829,7 +842,9 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     e2.s_row = p.s_ra; e2.s_col = p.s_b;
     e2.D_int = dbg ? dbg->DR2_int : nullptr;
     e2.final_scale = scale_needed;
-    if (path_b == 1) {
+    if (pair) {
+      // (term 2 went with term 1)
+    } else if (path_b == 1) {
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
       SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.b_ptr, nullptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, e2, st));
     } else if (path_b == 2) {

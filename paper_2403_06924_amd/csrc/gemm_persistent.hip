@@ -15,6 +15,7 @@
 //    landing in LDS (they need no registers), and the epilogue's stores retire while the next
 //    tile is multiplied.  A one-tile-per-workgroup launch pays launch, prologue latency and
 //    drain once per tile - four times per CU at 8192^3, since only one workgroup fits a CU.
+#include <type_traits>
 #include "srq_internal.h"
 #include "gemm_tiles.h"
 
@@ -37,7 +38,7 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
                                                                  const int8_t* __restrict__ Qa, int64_t lda,
                                                                  const int8_t* __restrict__ Qb, int64_t ldb,
                                                                  int64_t tiles_m, int64_t tiles_n,
-                                                                 GemmEpilogue ep) {
+                                                                 GemmEpilogue ep, GemmSecond sec) {
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
   float* sc_row = reinterpret_cast<float*>(lds + kLdsScales);
   float* sc_col = sc_row + BM;
@@ -49,31 +50,47 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   asm volatile("" : "+v"(tid));                     // keeps per-thread offsets from being hoisted out of the tile loop
   const int lane = tid & 63, w = tid >> 6, wm = w >> 1, wn = w & 1;
   const int64_t total = tiles_m * tiles_n, G = gridDim.x, nk = K / BK;
+  // accumulate mode may carry a second product over the same tiles (sec.Qa != null): a workgroup
+  // then runs product 0 and product 1 of a tile back to back, so that the tile of C written by
+  // the first is still in the caches when the second adds to it
+  const int nprod = (MODE == kGemmAccum && sec.Qa) ? 2 : 1;
 
   // ---- loader: wave w fetches rows 64w .. 64w+63 of each operand tile, eight rows per load.
   // Lane l of load j covers row 64w + 8j + l/8 and LDS piece l%8, which holds the logical piece
   // (l%8) ^ ((row >> 1) & 7); (row >> 1) & 7 = ((l >> 4) + 4j) & 7 depends on j only through
   // its parity.
   const int lrow = lane >> 3;
-  const int64_t goff_a0 = (int64_t)lrow * lda + 16 * ((lane & 7) ^ ((lane >> 4) & 7));
-  const int64_t goff_a1 = (int64_t)lrow * lda + 16 * ((lane & 7) ^ (((lane >> 4) + 4) & 7));
-  const int64_t goff_b0 = (int64_t)lrow * ldb + 16 * ((lane & 7) ^ ((lane >> 4) & 7));
-  const int64_t goff_b1 = (int64_t)lrow * ldb + 16 * ((lane & 7) ^ (((lane >> 4) + 4) & 7));
   int64_t vba = blockIdx.x, kta = 0;                // cursor of the K-tile being fetched
+  int proda = 0;                                    // ... and the product it belongs to
   const int8_t *pa, *pb;                            // row 64w of that K-tile in A and in B
+  int64_t cur_lda = lda, cur_ldb = ldb;
+  int64_t goff_a0 = 0, goff_a1 = 0, goff_b0 = 0, goff_b1 = 0;
   auto point = [&]() {
     int64_t tm, tn;
     tile_of(vba, tiles_m, tiles_n, tm, tn);
-    pa = Qa + (tm * BM + 64 * w) * lda + kta * BK;
-    pb = Qb + (tn * BN + 64 * w) * ldb + kta * BK;
+    const int8_t* A0 = proda ? sec.Qa : Qa;
+    const int8_t* B0 = proda ? sec.Qb : Qb;
+    cur_lda = proda ? sec.lda : lda;
+    cur_ldb = proda ? sec.ldb : ldb;
+    goff_a0 = (int64_t)lrow * cur_lda + 16 * ((lane & 7) ^ ((lane >> 4) & 7));
+    goff_a1 = (int64_t)lrow * cur_lda + 16 * ((lane & 7) ^ (((lane >> 4) + 4) & 7));
+    goff_b0 = (int64_t)lrow * cur_ldb + 16 * ((lane & 7) ^ ((lane >> 4) & 7));
+    goff_b1 = (int64_t)lrow * cur_ldb + 16 * ((lane & 7) ^ (((lane >> 4) + 4) & 7));
+    pa = A0 + (tm * BM + 64 * w) * cur_lda + kta * BK;
+    pb = B0 + (tn * BN + 64 * w) * cur_ldb + kta * BK;
   };
   auto advance = [&]() {
     if (kta + 1 < nk) {
       ++kta;
       pa += BK;
       pb += BK;
+    } else if (proda + 1 < nprod) {
+      ++proda;
+      kta = 0;
+      point();
     } else if (vba + G < total) {
       vba += G;
+      proda = 0;
       kta = 0;
       point();
     }                                               // else stay on the last K-tile (harmless re-fetch)
@@ -84,9 +101,9 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
     const uint32_t la = __builtin_amdgcn_readfirstlane(lds0 + stage * kStage + (64 * w) * BK);
     const int j = i >> 1;
     if (i & 1)
-      load_to_lds(pb + (int64_t)(8 * j) * ldb + ((j & 1) ? goff_b1 : goff_b0), la + kOperand + j * 8 * BK);
+      load_to_lds(pb + (int64_t)(8 * j) * cur_ldb + ((j & 1) ? goff_b1 : goff_b0), la + kOperand + j * 8 * BK);
     else
-      load_to_lds(pa + (int64_t)(8 * j) * lda + ((j & 1) ? goff_a1 : goff_a0), la + j * 8 * BK);
+      load_to_lds(pa + (int64_t)(8 * j) * cur_lda + ((j & 1) ? goff_a1 : goff_a0), la + j * 8 * BK);
   };
   auto issue_loads = [&](int stage) {
 #pragma unroll
@@ -134,7 +151,8 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
 
   const int64_t my_tiles = (total - blockIdx.x + G - 1) / G;
   int g = 0;                                        // parity of the K-tile stream across tiles
-  for (int64_t tile = 0; tile < my_tiles; ++tile) {
+  int prod = 0;                                     // product being multiplied (pairs: 0, 1, 0, 1, ...)
+  for (int64_t tile = 0; tile < my_tiles * nprod; ++tile) {
   for (int64_t kt = 0; kt < nk; ++kt, ++g) {
     const int cur = g & 1;
 #pragma unroll
@@ -189,6 +207,11 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
       colsum[b] = 0.0;
       scol[b] = sc_col[cbase + b * 32];
     }
+    // C goes around the caches (it would evict the FP32 operands the next stages stream), except
+    // between the two products of a pair: the first leaves its tile cached for the second
+    const bool do_scale = SCALE && prod == nprod - 1;
+    auto bands = [&](auto cached_load_tag, auto cached_store_tag) {
+    constexpr bool CLOAD = decltype(cached_load_tag)::value, CSTORE = decltype(cached_store_tag)::value;
 #pragma unroll
     for (int a = 0; a < TM; ++a) {
       const int rbase = wm * (BM / 2) + a * 32 + 4 * half;
@@ -198,8 +221,10 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
 #pragma unroll
         for (int v = 0; v < 16; ++v)
 #pragma unroll
-          for (int b = 0; b < TN; ++b)
-            x[b][v] = __builtin_nontemporal_load(&cband[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32]);
+          for (int b = 0; b < TN; ++b) {
+            const float* src = &cband[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32];
+            x[b][v] = CLOAD ? *src : __builtin_nontemporal_load(src);
+          }
       }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -209,11 +234,12 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
         for (int b = 0; b < TN; ++b) {
           const float d = (float)acc[a][b][v] * (srow * scol[b]);
           float out = MODE == kGemmFirst ? d : x[b][v] + d;
-          if (SCALE) {
+          if (SCALE && do_scale) {
             out = ep.alpha * out;
             if (ep.beta != 0.f) out = out + ep.beta * ep.Cin[(m0 + rbase + ro) * ep.ldcin + n0 + cbase + b * 32];
           }
-          __builtin_nontemporal_store(out, &cband[(int64_t)ro * ep.ldc + b * 32]);
+          if (CSTORE) cband[(int64_t)ro * ep.ldc + b * 32] = out;
+          else __builtin_nontemporal_store(out, &cband[(int64_t)ro * ep.ldc + b * 32]);
           if (SUMS) x[b][v] = fabsf(d);
           acc[a][b][v] = 0;
         }
@@ -248,6 +274,10 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    };
+    if (nprod == 2 && prod == 0) bands(std::false_type(), std::true_type());
+    else if (nprod == 2) bands(std::true_type(), std::false_type());
+    else bands(std::false_type(), std::false_type());
     if (SUMS) {
       __syncthreads();
       ep.row_part[tile_n * M + m0 + tid] = red[tid] + red[256 + tid];
@@ -261,12 +291,19 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
       __syncthreads();
       ep.col_part[tile_m * N + n0 + tid] = red[tid] + red[256 + tid];
     }
-    // next output tile of this workgroup
-    vb += G;
-    if (vb < total) {
-      tile_of(vb, tiles_m, tiles_n, tile_m, tile_n);
-      sreg_row = ep.s_row[tile_m * BM + tid];
-      sreg_col = ep.s_col[tile_n * BN + tid];
+    // next product of this tile, or the next output tile of this workgroup
+    if (prod + 1 < nprod) {
+      prod = 1;
+      sreg_row = sec.s_row[tile_m * BM + tid];
+      sreg_col = sec.s_col[tile_n * BN + tid];
+    } else {
+      prod = 0;
+      vb += G;
+      if (vb < total) {
+        tile_of(vb, tiles_m, tiles_n, tile_m, tile_n);
+        sreg_row = ep.s_row[tile_m * BM + tid];
+        sreg_col = ep.s_col[tile_n * BN + tid];
+      }
     }
   }
   wait_loads();                                     // nothing may still be writing LDS when the wave ends
@@ -302,7 +339,8 @@ hipError_t gemm_device_cus(int* cus) {
 }
 
 hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
-                                     const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st) {
+                                     const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st,
+                                     const GemmSecond* second) {
   int num_cu = 0;
   hipError_t e = gemm_device_cus(&num_cu);
   if (e != hipSuccess) return e;
@@ -313,7 +351,9 @@ hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8
   const bool sums = ep.mode == kGemmFirst && ep.row_part != nullptr;
   const bool scale = ep.final_scale != 0;
   void (*kern)(int64_t, int64_t, int64_t, const int8_t*, int64_t, const int8_t*, int64_t, int64_t, int64_t,
-               GemmEpilogue);
+               GemmEpilogue, GemmSecond);
+  GemmSecond sec = {nullptr, nullptr, 0, 0, nullptr, nullptr};
+  if (second && ep.mode == kGemmAccum) sec = *second;
   if (ep.mode == kGemmFirst) {
     kern = sums ? (scale ? gemm_i8_persistent_kernel<kGemmFirst, true, true>
                          : gemm_i8_persistent_kernel<kGemmFirst, true, false>)
@@ -333,7 +373,8 @@ hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8
     for (auto& p : attr_done)
       if (!p) { p = reinterpret_cast<const void*>(kern); break; }
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), kLdsBytes, st, M, N, K, Qa, lda, Qb, ldb, tm, tn, ep);
+  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), kLdsBytes, st, M, N, K, Qa, lda, Qb, ldb, tm, tn, ep,
+                     sec);
   return hipGetLastError();
 }
 

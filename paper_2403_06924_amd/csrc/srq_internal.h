@@ -49,6 +49,17 @@ struct GemmEpilogue {
   int64_t ldcin;
 };
 
+// Second product of a paired accumulate-mode launch of the persistent kernel: C += dequant(Qa.Qb^T)
+// with its own scales, right after the first product of the same output tile (Qa == null: none).
+// alpha / beta of the epilogue, if any, are applied after the second product.
+struct GemmSecond {
+  const int8_t* Qa;
+  const int8_t* Qb;
+  int64_t lda, ldb;
+  const float* s_row;
+  const float* s_col;
+};
+
 // ---- launchers (each returns the hipError_t of its launches) --------------------------
 hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
 
@@ -167,8 +178,10 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int
 hipError_t gemm_device_cus(int* cus);
 bool gemm_persistent_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb,
                         int64_t ldb, const GemmEpilogue& ep);
+// (second: accumulate mode only; both products must pass gemm_persistent_ok)
 hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
-                                     const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st);
+                                     const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st,
+                                     const GemmSecond* second = nullptr);
 
 // CSR (vector-major) -> zero-filled dense vector-major codes
 hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* val, int64_t nvec,
