@@ -240,7 +240,8 @@ def test_persistent_gemm_uneven_tile_counts(srq, b, shape):
 def test_padded_inner_dimension_through_persistent_kernels(srq, b, shape, variant):
     """K that is no multiple of 64 with M, N multiples of 256: the code matrices are padded to a
     leading dimension of 256 with zero columns and the persistent kernels run on the padded K.
-    The timed configuration (no debug outputs), every path, element by element, with alpha."""
+    The timed configuration (no debug outputs), every path, element by element, with alpha and beta
+    (on the matrix-core paths both terms share one launch, which applies them after the second)."""
     M, N, K = shape
     rng = np.random.default_rng(M + N + K)
     A = (rng.standard_normal((M, K)) * np.exp(rng.standard_normal((M, 1)))).astype(F32)
@@ -251,14 +252,16 @@ def test_padded_inner_dimension_through_persistent_kernels(srq, b, shape, varian
     ta = wl.theta_for_density(A, drow, "row", density)
     tb = wl.theta_for_density(B, dcol, "col", density)
     stats = b.stats_tensor()
+    Cin = rng.standard_normal((M, N)).astype(F32)
     C, _, _ = srq.compensated_gemm(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), ta, tb, strategy=strategy,
-                                   dense_fallback_density=s, stats=stats, alpha=0.5)
+                                   dense_fallback_density=s, stats=stats, alpha=0.5, beta=-0.75,
+                                   C_in=torch.from_numpy(Cin).cuda())
     torch.cuda.synchronize()
     im = srq.intermediates(M, N, K)
     st = b.read_stats(stats)
     assert im["ld_codes"] == 256
-    ref = o.compensated_gemm(A, B, ta, tb, alpha=0.5, dense_fallback_density=s, thresh_a=host(im["t_a"]),
-                             thresh_b=host(im["t_b"]))
+    ref = o.compensated_gemm(A, B, ta, tb, alpha=0.5, beta=-0.75, C_in=Cin, dense_fallback_density=s,
+                             thresh_a=host(im["t_a"]), thresh_b=host(im["t_b"]))
     assert st["path_a"] == st["path_b"] == {"mfma": 2, "auto_sparse": 1, "dense_branch": 3}[variant]
     assert (host(im["A_int"]) == ref.A_int).all() and (host(im["B_int"]) == ref.B_int.T).all()
     assert st["nnz_a"] == ref.csr_a.nnz and st["nnz_b"] == ref.csc_b.nnz
