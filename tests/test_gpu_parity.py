@@ -344,7 +344,7 @@ def test_auto_repeated_calls_reuse_the_previous_choice(srq, b):
         assert st["path_a"] == st["path_b"] == (1 if density < 0.005 else 2)
 
 
-@pytest.mark.parametrize("shape", [(256, 256, 256), (512, 768, 384), (768, 512, 200), (256, 512, 1000)])
+@pytest.mark.parametrize("shape", [(256, 256, 256), (512, 768, 384), (768, 512, 200), (256, 512, 1000), (256, 256, 9000)])
 @pytest.mark.parametrize("density", [0.05, 0.3])
 def test_structured_2to4_execution(srq, b, shape, density):
     """SRQ_STRATEGY_CSR_SMFMAC: the reduced operand is split into a 2:4 operand for the sparse
