@@ -30,8 +30,7 @@ constexpr int kOperand = BM * BK;                   // 32 KiB per operand tile
 constexpr int kStage = 2 * kOperand;                // A tile then B tile
 constexpr int TM = 4, TN = 4;                       // 32x32 MFMA tiles per wave
 constexpr int kLdsScales = 2 * kStage;              // float[BM + BN]
-constexpr int kLdsRed = kLdsScales + (BM + BN) * 4; // double[2][256]
-constexpr int kLdsBytes = kLdsRed + 2 * 256 * 8;
+constexpr int kLdsBytes = kLdsScales + (BM + BN) * 4;
 
 template <int MODE, bool SUMS, bool SCALE>
 __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int64_t N, int64_t K,
@@ -42,7 +41,6 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
   float* sc_row = reinterpret_cast<float*>(lds + kLdsScales);
   float* sc_col = sc_row + BM;
-  double* red = reinterpret_cast<double*>(lds + kLdsRed);
   // LDS byte address of the first stage (an address-space-3 pointer is a 32-bit offset)
   const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) int8_t*)lds);
 
@@ -261,7 +259,9 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
         }
         r[0] += __shfl_xor(r[0], 1, 64);
         const int v = cl >> 1;
-        if (!(cl & 1)) red[wn * 256 + rbase + 8 * (v >> 2) + (v & 3)] = (double)r[0];
+        // each wave leaves its own partial (its 128 columns of the tile): no exchange through LDS
+        // and no barrier, so a wave that is done starts on the next tile
+        if (!(cl & 1)) ep.row_part[(2 * tile_n + wn) * M + m0 + rbase + 8 * (v >> 2) + (v & 3)] = (double)r[0];
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
           float t8[8], t4[4];
@@ -279,17 +279,12 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
     else if (nprod == 2) bands(std::true_type(), std::false_type());
     else bands(std::false_type(), std::false_type());
     if (SUMS) {
-      __syncthreads();
-      ep.row_part[tile_n * M + m0 + tid] = red[tid] + red[256 + tid];
-      __syncthreads();
 #pragma unroll
       for (int b = 0; b < TN; ++b) {
         double c = colsum[b];
         c += __shfl_xor(c, 32, 64);
-        if (half == 0) red[wm * 256 + cbase + b * 32] = c;
+        if (half == 0) ep.col_part[(2 * tile_m + wm) * N + n0 + cbase + b * 32] = c;
       }
-      __syncthreads();
-      ep.col_part[tile_m * N + n0 + tid] = red[tid] + red[256 + tid];
     }
     // next product of this tile, or the next output tile of this workgroup
     if (prod + 1 < nprod) {
