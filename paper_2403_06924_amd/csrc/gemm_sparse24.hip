@@ -53,12 +53,12 @@ __global__ __launch_bounds__(256) void gemm_i8_sparse24_kernel(int64_t M, int64_
   // ---- loader.  Wave w fetches rows 64w .. 64w+63 of each operand tile.
   //  codes:     4 loads of 16 rows; lane l covers row 16j + l/4 and LDS slot l%4, which holds the
   //             logical piece (l%4) ^ ((row >> 2) & 3) = (l%4) ^ ((l >> 4) & 3)
-  //  positions: 1 load, lane l covers the 16 bytes of row l
+  //  positions: 1 load, a quarter of the tile's 4 KiB (word planes, see sparse24.hip)
   //  dense:     8 loads of 8 rows as in the dense kernel
   // (the 2:4 operand is stored K-tile-major per block of 256 vectors: a staged tile is one
   // contiguous piece of memory, 64 resp. 16 bytes per vector)
   const int64_t goff_v = (int64_t)(lane >> 2) * (BK / 2) + 16 * ((lane & 3) ^ ((lane >> 4) & 3));
-  const int64_t goff_n = (int64_t)lane * (BK / 8);
+  const int64_t goff_n = (int64_t)lane * 16;        // the 4 KiB of nibbles of a tile are copied as they are
   const int lrow = lane >> 3;
   const int64_t goff_b0 = (int64_t)lrow * ldb + 16 * ((lane & 7) ^ ((lane >> 4) & 7));
   const int64_t goff_b1 = (int64_t)lrow * ldb + 16 * ((lane & 7) ^ (((lane >> 4) + 4) & 7));
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void gemm_i8_sparse24_kernel(int64_t M, int64_
     int64_t tm, tn;
     tile_of(vba, tiles_m, tiles_n, tm, tn);
     pv = Av + ((tm * nk + kta) * BM + 64 * w) * (BK / 2);
-    pn = An + ((tm * nk + kta) * BM + 64 * w) * (BK / 8);
+    pn = An + (tm * nk + kta) * kNibs + 1024 * w;
     pb = Qb + (tn * BN + 64 * w) * ldb + kta * BK;
   };
   auto advance = [&]() {
@@ -109,13 +109,14 @@ __global__ __launch_bounds__(256) void gemm_i8_sparse24_kernel(int64_t M, int64_
   const int frow = lane & 31, kh = lane >> 5;
   const int key_v = (frow >> 2) & 3, key_b = (frow >> 1) & 7;
   const int v_row = (wm * (BM / 2) + frow) * (BK / 2);
-  const int n_row = kVals + (wm * (BM / 2) + frow) * (BK / 8);
+  // (position words: plane-major, vectors of the odd planes rotated by 32; plane = 2 step + kh)
+  const int n_row = kVals + 4 * ((wm * (BM / 2) + frow) ^ (32 * kh));
   const int b_row = kVals + kNibs + (wn * (BN / 2) + frow) * BK;
   int xv[KS], xn[KS], xb0[KS], xb1[KS];
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
     xv[s] = 16 * ((2 * s + kh) ^ key_v);
-    xn[s] = 4 * (2 * s + kh);
+    xn[s] = 4 * 256 * (2 * s + kh);
     xb0[s] = 16 * ((4 * s + 2 * kh) ^ key_b);
     xb1[s] = 16 * ((4 * s + 2 * kh + 1) ^ key_b);
   }
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(256) void gemm_i8_sparse24_kernel(int64_t M, int64_
 #pragma unroll
     for (int t = 0; t < TM; ++t) {
       fa[slot][t] = *reinterpret_cast<const v4i*>(base + v_row + t * 32 * (BK / 2) + xv[step]);
-      fi[slot][t] = *reinterpret_cast<const int*>(base + n_row + t * 32 * (BK / 8) + xn[step]);
+      fi[slot][t] = *reinterpret_cast<const int*>(base + (n_row ^ (4 * 32 * (t & 1))) + 4 * 32 * (t & ~1) + xn[step]);
     }
 #pragma unroll
     for (int t = 0; t < TN; ++t) {

@@ -12,9 +12,12 @@
 //     piece the indices ascend).
 // Layout of the 2:4 operand: K-tile-major inside blocks of 256 vectors, the unit the matrix-core
 // kernel stages: the 64 code bytes (16 nibble bytes) that vector v holds for the K-tile t of
-// 128 k sit at ((v / 256) * (kc / 128) + t) * 256 * 64 + (v % 256) * 64 (resp. ... * 16), so that
-// one staged tile is one contiguous 16 KiB (4 KiB) piece of memory.  The vector count is padded
-// to a multiple of 256 by the caller's buffers.
+// 128 k sit at ((v / 256) * (kc / 128) + t) * 256 * 64 + (v % 256) * 64, so that one staged tile
+// is one contiguous 16 KiB piece of memory; the 4 KiB of nibbles of a tile are stored as four
+// planes of 256 32-bit words, plane c holding the positions of code bytes 16c .. 16c+15 of every
+// vector, vector r at word r ^ 32 in the odd planes (the 64 lanes of a wave, which read the
+// words of 32 consecutive vectors from two neighbouring planes, then hit 64 different LDS
+// banks).  The vector count is padded to a multiple of 256 by the caller's buffers.
 // Byte order of the 2:4 operand inside every block of 64 k: the four groups of k 0-15, then
 // those of k 32-47, 16-31, 48-63 (eight bytes each; the nibbles in the same order).  This is
 // the order in which v_smfmac_i32_32x32x64_i8 consumes them: the lane that holds row r and
@@ -132,7 +135,11 @@ __global__ __launch_bounds__(256) void compress24_kernel(const int8_t* __restric
       const int64_t tile = (v >> 8) * (kc >> 7) + (blk >> 1);
       const int64_t in_tile = v & 255;
       *reinterpret_cast<u2v*>(vals + (tile * 256 + in_tile) * 64 + 32 * (blk & 1) + 8 * ord) = o;
-      *reinterpret_cast<uint16_t*>(nib + (tile * 256 + in_tile) * 16 + 8 * (blk & 1) + 2 * ord) = (uint16_t)nibs;
+      // positions: word c = 2 (blk & 1) + ord / 2 of the vector, stored word-plane-major with the
+      // vectors of the odd planes rotated by 32 (see the layout note above)
+      const int c = 2 * (int)(blk & 1) + (ord >> 1);
+      const int64_t word = c * 256 + (in_tile ^ ((c & 1) << 5));
+      *reinterpret_cast<uint16_t*>(nib + tile * 4096 + 4 * word + 2 * (ord & 1)) = (uint16_t)nibs;
     }
     if (!total) return;                                            // (wave-uniform) nothing of this vector spills
     // spilled entries in ascending k: lanes in order, then position
