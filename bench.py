@@ -185,7 +185,10 @@ def main():
         roof = {"kernel": "gemm_i8_persistent_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_INT8_TOPS,
                 "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS, "traffic": recorded_traffic(args.workload),
                 "products_per_step": len(gemm_ms), "launches_per_step": sum(1 for t in gemm_ms if t > 0),
-                "avg_product_ms": avg}
+                "avg_product_ms": avg,
+                # context, not the roofline: what a register-resident loop of the same instruction
+                # sustained on this chip with random operand bytes (it reaches 4950 on zeros)
+                "mfma_sustained_random_operands": 3440.0}
     else:
         t = sum(t for t, _ in valu_ms)
         macs = sum(m for _, m in valu_ms)
