@@ -44,31 +44,20 @@ def parse():
 
 
 def recorded_traffic(workload):
-    """HBM bytes per GEMM launch from the committed rocprofv3 counter summary of this workload
-    (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy); None when no summary exists."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
-                        "bench_%s_hbm_traffic.md" % workload)
+    """HBM bytes per first-product launch from the committed rocprofv3 counter summary of this
+    workload (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy) and where the figure comes
+    from; (None, None) when no summary exists.  bench.py cannot run the profiler on itself, so the
+    figure is recorded, not measured in this run: `traffic_source` in the JSON line says so."""
+    rel = os.path.join("profiles", "bench_%s_hbm_traffic.md" % workload)
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), rel)
     try:
         with open(path) as f:
             for line in f:
                 if line.startswith("TRAFFIC_BYTES_PER_GEMM_LAUNCH"):
-                    return int(line.split("=")[1])
+                    return int(line.split("=")[1]), rel + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE; recorded, not measured in this run)"
     except OSError:
         pass
-    return None
-
-
-def calibrate_theta(torch, X, dvec, axis, density):
-    """Harness only: theta such that about `density` of the entries have |x| > theta*dvec."""
-    d = dvec.view(-1, 1) if axis == 0 else dvec.view(1, -1)
-    rho = (X.abs() / d).reshape(-1)
-    keep = int(round(rho.numel() * density))
-    if keep <= 0:
-        return float("inf")
-    if keep >= rho.numel():
-        return 0.0
-    k = rho.numel() - keep
-    return float(torch.sort(rho).values[k - 1].item())       # k-th smallest; a sort is far faster than kthvalue here
+    return None, None
 
 
 def cpu_baseline(name, A, B, theta_a, theta_b):
@@ -131,8 +120,8 @@ def main():
     Qa, sa, _ = h.quantize(Ad, b.AXIS_ROW)
     Qb, sb, _ = h.quantize(Bd, b.AXIS_COL)
     _, _, drow, dcol = h.gemm_i8(Qa, sa, Qb, sb)
-    theta_a = calibrate_theta(torch, Ad, drow, 0, density)
-    theta_b = calibrate_theta(torch, Bd, dcol, 1, density)
+    theta_a = wl.theta_for_density(Ad, drow, 0, density)
+    theta_b = wl.theta_for_density(Bd, dcol, 1, density)
     del Qa, Qb
     torch.cuda.empty_cache()
 
@@ -167,35 +156,56 @@ def main():
     ops = 2.0 * M * N * K
     value = ops / (ms_per_step * 1e-3) / 1e12
 
-    # roofline of the dominant kernel.  The INT8 GEMM kernel runs once for the first product
-    # and once per correction term that takes a matrix-core path (2 = expanded CSR, 3 = dense)
-    gemm_ms = [stage_ms["gemm"]]
-    valu_ms = []
-    for term, path in (("term1", st["path_a"]), ("term2", st["path_b"])):
+    # ---- roofline.  Two kinds of launches of the matrix-core kernel make up a step:
+    #  * the first product (a2 + a3 + a4): a dense contraction, 2MNK integer operations, against
+    #    the dense INT8 matrix-core peak.  This is the `roofline` entry proper.
+    #  * the correction launch(es) (a7 + a8).  The method's own work there is
+    #    2 (nnz_A N + nnz_B M) operations (the sparse products of Algorithm 1 line 12); what the
+    #    chosen execution actually issues is reported next to it: on the dense matrix-core kernel
+    #    (paths 2, 3) every term issues a full 2MNK, of which the zero-filled part multiplies zeros;
+    #    on the 2:4 kernel (path 4) a term issues half of that; on the vector ALUs (path 1) only the
+    #    method's own operations are issued.
+    # Times are HIP events recorded by the library on the launch stream around each stage, inside
+    # the timed region (srq_profile_enable).
+    gemm_ms = stage_ms["gemm"]
+    ach = ops / (gemm_ms * 1e-3) / 1e12
+    traffic, traffic_src = recorded_traffic(args.workload)
+    roof = {"kernel": "gemm_i8_persistent_kernel, first product (a2+a3+a4)", "bound": "mfma", "achieved": ach,
+            "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS, "launch_ms": gemm_ms,
+            "ops_per_launch": ops, "traffic": traffic, "traffic_source": traffic_src,
+            # context, not the roofline: what a register-resident loop of the same instruction
+            # sustained on this chip with random operand bytes (it reaches 4950 on zeros)
+            "mfma_sustained_random_operands": 3440.0}
+    own_ops = 2.0 * (st["nnz_a"] * N + st["nnz_b"] * M)
+    corr_ms = sum(stage_ms[k] for k in ("term1_prep", "term1", "term2_prep", "term2"))
+    issued, units = 0.0, set()
+    for path, own in ((st["path_a"], 2.0 * st["nnz_a"] * N), (st["path_b"], 2.0 * st["nnz_b"] * M)):
         if path in (2, 3):
-            gemm_ms.append(stage_ms[term])
+            issued += ops
+            units.add("mfma")
+        elif path == 4:
+            issued += ops / 2
+            units.add("smfmac")
         elif path == 1:
-            valu_ms.append((stage_ms[term], st["nnz_a"] * N if term == "term1" else st["nnz_b"] * M))
-    if sum(gemm_ms) >= sum(t for t, _ in valu_ms):
-        # unit of work: one product of 2MNK operations.  When both correction terms take a
-        # matrix-core path they share one launch (the two products of a tile back to back), whose
-        # time is booked under term1: 3 products in 2 launches
-        avg = sum(gemm_ms) / len(gemm_ms)
-        ach = ops / (avg * 1e-3) / 1e12
-        roof = {"kernel": "gemm_i8_persistent_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_INT8_TOPS,
-                "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS, "traffic": recorded_traffic(args.workload),
-                "products_per_step": len(gemm_ms), "launches_per_step": sum(1 for t in gemm_ms if t > 0),
-                "avg_product_ms": avg,
-                # context, not the roofline: what a register-resident loop of the same instruction
-                # sustained on this chip with random operand bytes (it reaches 4950 on zeros)
-                "mfma_sustained_random_operands": 3440.0}
-    else:
-        t = sum(t for t, _ in valu_ms)
-        macs = sum(m for _, m in valu_ms)
-        ach = 2.0 * macs / (t * 1e-3) / 1e12
-        roof = {"kernel": "spmm_tile_kernel", "bound": "alu", "achieved": ach, "peak": PEAK_VALU_INT_TOPS,
-                "unit": "TOP/s", "frac": ach / PEAK_VALU_INT_TOPS, "traffic": None,
-                "launches_per_step": len(valu_ms), "avg_launch_ms": t / len(valu_ms)}
+            issued += own
+            units.add("valu")
+    corr = None
+    if corr_ms > 0:
+        on_valu = units == {"valu"}
+        peak = PEAK_VALU_INT_TOPS if on_valu else PEAK_INT8_TOPS
+        corr = {"stages": "a7+a8 (both correction terms" + (", one paired launch)" if stage_ms["term2"] == 0
+                                                            and st["path_b"] else ")"),
+                "executed_on": sorted(units), "launch_ms": corr_ms,
+                "own_work_ops": own_ops, "own_work_achieved": own_ops / (corr_ms * 1e-3) / 1e12,
+                "peak": peak, "unit": "TOP/s",
+                "own_work_frac": own_ops / (corr_ms * 1e-3) / 1e12 / peak,
+                "issued_ops": issued, "issued_frac": issued / (corr_ms * 1e-3) / 1e12 / peak,
+                "zero_fraction_of_sparse_operands": 1.0 - (st["nnz_a"] + st["nnz_b"]) / float(M * K + N * K)}
+    roof["corrections"] = corr
+    # the products of a whole step on their own work: first product + the method's sparse products
+    prod_ms = gemm_ms + corr_ms
+    roof["products_own_work"] = {"ops": ops + own_ops, "ms": prod_ms,
+                                 "frac_of_int8_mfma_peak": (ops + own_ops) / (prod_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS}
 
     accuracy = None
     if not args.no_accuracy:

@@ -85,6 +85,11 @@ typedef struct srq_stats_t {
   int64_t nnz_b;        /* entries kept in B'                                               */
   int32_t path_a;       /* 0 = term skipped (theta = inf), 1 = CSR_VALU, 2 = CSR_MFMA,      */
   int32_t path_b;       /* 3 = dense branch on the unreduced operand, 4 = CSR_SMFMAC        */
+  int32_t overflow;     /* bit 0: A' kept more entries than the workspace's compressed      */
+                        /* arrays hold, bit 1: the same for B'.  Non-zero means that NO      */
+                        /* correction term was added: C holds the uncorrected first product  */
+                        /* (alpha / beta not applied), as with SRQ_STATUS_CAPACITY           */
+  int32_t reserved;     /* written as 0                                                     */
 } srq_stats_t;
 
 /* Optional extra outputs of srq_compensated_gemm for stage-by-stage checks; any member may
@@ -246,8 +251,11 @@ srq_status_t srq_spmm_accumulate(srq_handle_t handle, srq_axis_t side, srq_strat
  * recorded into a HIP graph by a capturing caller (the workspace must be attached before).
  * Returns SRQ_STATUS_CAPACITY (after the first product and the selection ran: C then holds the
  * uncorrected D_F, no correction term was added) when a synchronising mode finds more kept
- * entries than the workspace was sized for; in non-synchronising
- * modes the compressed arrays are truncated instead and stats_dev tells. */
+ * entries than the workspace was sized for.  A non-synchronising mode cannot know on the host:
+ * it returns SRQ_STATUS_OK, every correction kernel checks the counts on the device and does
+ * nothing when an operand overflowed, so that C again holds the uncorrected D_F (never a
+ * correction from truncated arrays), and stats_dev->overflow is set: pass stats_dev and check
+ * it after synchronising.  The compressed arrays themselves hold the first `capacity` entries. */
 srq_status_t srq_compensated_gemm(srq_handle_t handle, int64_t M, int64_t N, int64_t K, const float* A,
                                   int64_t lda, const float* B, int64_t ldb, float theta_a, float theta_b,
                                   int bits, srq_round_t round, float dense_fallback_density,

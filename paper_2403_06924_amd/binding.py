@@ -32,7 +32,8 @@ STAGES = ["quantize", "gemm", "select", "residual", "term1_prep", "term1", "term
 
 
 class Stats(C.Structure):
-    _fields_ = [("nnz_a", C.c_int64), ("nnz_b", C.c_int64), ("path_a", C.c_int32), ("path_b", C.c_int32)]
+    _fields_ = [("nnz_a", C.c_int64), ("nnz_b", C.c_int64), ("path_a", C.c_int32), ("path_b", C.c_int32),
+                ("overflow", C.c_int32), ("reserved", C.c_int32)]
 
 
 class Debug(C.Structure):
@@ -321,13 +322,15 @@ class Srq:
 
 
 def stats_tensor(device="cuda:0"):
-    """Device buffer laid out as srq_stats_t: int64 nnz_a, nnz_b, then int32 path_a, path_b."""
+    """Device buffer laid out as srq_stats_t: int64 nnz_a, nnz_b, then int32 path_a, path_b,
+    overflow, reserved."""
     import torch
-    return torch.zeros(3, dtype=torch.int64, device=device)
+    return torch.zeros(C.sizeof(Stats) // 8, dtype=torch.int64, device=device)
 
 
 def read_stats(t):
     """Decode a stats tensor written by srq_compensated_gemm (synchronises)."""
     host = t.cpu()
-    paths = host[2:3].view(dtype=__import__("torch").int32)
-    return {"nnz_a": int(host[0]), "nnz_b": int(host[1]), "path_a": int(paths[0]), "path_b": int(paths[1])}
+    words = host[2:4].view(dtype=__import__("torch").int32)
+    return {"nnz_a": int(host[0]), "nnz_b": int(host[1]), "path_a": int(words[0]), "path_b": int(words[1]),
+            "overflow": int(words[2])}

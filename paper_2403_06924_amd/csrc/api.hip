@@ -27,6 +27,8 @@ inline int strategy_path(srq_strategy_t s) {
   return s == SRQ_STRATEGY_CSR_VALU ? kPathValu : s == SRQ_STRATEGY_CSR_SMFMAC ? kPath24 : kPathMfma;
 }
 
+constexpr int64_t kNoCap = INT64_MAX;     // capacity of an operand that is not compacted
+
 constexpr double kAutoMfmaDensityA = 0.012;
 constexpr double kAutoMfmaDensityALongK = 0.008;
 constexpr double kAutoMfmaDensityB = 0.009;
@@ -354,7 +356,12 @@ srq_status_t srq_quantize(srq_handle_t h, const float* X, int64_t rows, int64_t 
     if (lambda) SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(lambda), nvec, 0, st));
     return SRQ_STATUS_OK;
   }
-  if (axis == SRQ_AXIS_COL && cols_pass_ok(X, cols, ldx)) {
+  // (the column kernels store 16 codes of a vector, resp. 4 codes of a row, at a time: the
+  // caller's Q must be aligned for that, otherwise the generic kernels run)
+  const uintptr_t qaddr = reinterpret_cast<uintptr_t>(Q);
+  const bool q_ok = layout == SRQ_LAYOUT_VECTOR_MAJOR ? ((qaddr % 16) == 0 && (ldq % 16) == 0)
+                                                      : ((qaddr % 4) == 0 && (ldq % 4) == 0);
+  if (axis == SRQ_AXIS_COL && cols_pass_ok(X, cols, ldx) && q_ok) {
     const bool vm = layout == SRQ_LAYOUT_VECTOR_MAJOR;
     SRQ_HIP(h, launch_cols_amax(X, rows, cols, ldx, reinterpret_cast<uint32_t*>(scale), st));
     SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(scale), lam, nvec, qmax, st));
@@ -662,6 +669,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   }
   int path_a = 0, path_b = 0;
   if (comp) {
+    // line 9 and the branch of line 11 need the counts on the host in these modes
+    const bool sync_mode = strategy == SRQ_STRATEGY_AUTO || dense_fallback_density <= 1.f;
     {
     StageTimer tm(h, st, SRQ_STAGE_SELECT);
     // line 7: GetAvgVec, and the thresholds of Eq. avgQuan
@@ -706,7 +715,6 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     SRQ_HIP(h, launch_scan_pair(term_a ? p.tot_a : nullptr, M, p.a_ptr, p.nnz + 0,
                                 (term_b && fastB) ? p.tot_b : nullptr, N, p.b_ptr, p.nnz + 1, st));
     // line 9 and the branch of line 11: which execution each term takes
-    const bool sync_mode = strategy == SRQ_STRATEGY_AUTO || dense_fallback_density <= 1.f;
     int64_t known_a = -1, known_b = -1;        // kept entries, once the host has read them
     if (sync_mode) {
       h->host_nnz[0] = h->host_nnz[1] = 0;
@@ -728,7 +736,9 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       if (term_b && strategy == SRQ_STRATEGY_AUTO) h->last_path_b = path_b;
       // an operand on the dense branch is not compacted, so only the others need room
       if ((path_a != 3 && na > p.cap_a) || (path_b != 3 && nb > p.cap_b)) {
-        if (stats_dev) SRQ_HIP(h, launch_stats(term_a ? p.nnz : nullptr, term_b ? p.nnz + 1 : nullptr, 0, 0, stats_dev, st));
+        if (stats_dev)
+          SRQ_HIP(h, launch_stats(term_a ? p.nnz : nullptr, term_b ? p.nnz + 1 : nullptr, 0, 0,
+                                  path_a != 3 ? p.cap_a : kNoCap, path_b != 3 ? p.cap_b : kNoCap, stats_dev, st));
         return SRQ_STATUS_CAPACITY;
       }
     } else {
@@ -807,6 +817,13 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     e1.s_row = p.s_a; e1.s_col = p.s_rb;
     e1.D_int = dbg ? dbg->DR1_int : nullptr;
     e1.final_scale = scale_needed && path_b == 0;
+    if (!sync_mode) {
+      // the host has not seen the counts: every correction kernel checks them itself and leaves C
+      // alone if an operand kept more entries than its compressed arrays hold
+      e1.guard_nnz = p.nnz;
+      e1.guard_cap_a = (path_a && path_a != kPathDense) ? p.cap_a : kNoCap;
+      e1.guard_cap_b = (path_b && path_b != kPathDense) ? p.cap_b : kNoCap;
+    }
     // both terms on the dense matrix-core kernel: one launch, the two products of a tile back to
     // back (the tile of C is still cached when the second product adds to it)
     const int8_t* t1a = path_a == kPathMfma ? p.Ad : p.A_int;
@@ -877,7 +894,9 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     }
   }
   if (stats_dev)
-    SRQ_HIP(h, launch_stats(path_a ? p.nnz : nullptr, path_b ? p.nnz + 1 : nullptr, path_a, path_b, stats_dev, st));
+    SRQ_HIP(h, launch_stats(path_a ? p.nnz : nullptr, path_b ? p.nnz + 1 : nullptr, path_a, path_b,
+                            (path_a && path_a != kPathDense) ? p.cap_a : kNoCap,
+                            (path_b && path_b != kPathDense) ? p.cap_b : kNoCap, stats_dev, st));
   return SRQ_STATUS_OK;
 }
 

@@ -65,6 +65,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(int64_t M, int64_t N, int6
                                                       GemmEpilogue ep) {
   using C = Cfg<BM, BN, BK>;
   extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+  if (guard_tripped(ep)) return;                   // the whole grid leaves together
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int wm = w >> 1, wn = w & 1;
@@ -332,7 +333,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(int64_t M, int64_t N, int6
 // C = alpha*C + beta*Cin when no product term carries the final scaling
 __global__ void scale_only_kernel(int64_t M, int64_t N, GemmEpilogue ep) {
   int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= N) return;
+  if (j >= N || guard_tripped(ep)) return;
   for (int64_t i = blockIdx.y; i < M; i += gridDim.y) {
     float out = ep.alpha * ep.C[i * ep.ldc + j];
     if (ep.beta != 0.f) out = out + ep.beta * ep.Cin[i * ep.ldcin + j];
@@ -354,13 +355,9 @@ hipError_t launch_cfg(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t
   const bool dbg = ep.D_int != nullptr || ep.D_F_copy != nullptr;
   auto kern = dbg ? (fast ? gemm_i8_kernel<BM, BN, BK, true, true> : gemm_i8_kernel<BM, BN, BK, false, true>)
                   : (fast ? gemm_i8_kernel<BM, BN, BK, true, false> : gemm_i8_kernel<BM, BN, BK, false, false>);
-  static bool attr_done[4] = {false, false, false, false};
-  const int slot = (fast ? 1 : 0) + (dbg ? 2 : 0);
-  if (lds_bytes > 64 * 1024 && !attr_done[slot]) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (lds_bytes > 64 * 1024) {
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds_bytes);
     if (e != hipSuccess) return e;
-    attr_done[slot] = true;
   }
   hipLaunchKernelGGL(kern, grid, dim3(256), lds_bytes, st, M, N, K, Qa, lda, Qb, ldb, tm, tn, ep);
   return hipGetLastError();

@@ -15,7 +15,11 @@
 //    landing in LDS (they need no registers), and the epilogue's stores retire while the next
 //    tile is multiplied.  A one-tile-per-workgroup launch pays launch, prologue latency and
 //    drain once per tile - four times per CU at 8192^3, since only one workgroup fits a CU.
+#include <atomic>
+#include <mutex>
 #include <type_traits>
+#include <utility>
+#include <vector>
 #include "srq_internal.h"
 #include "gemm_tiles.h"
 
@@ -39,6 +43,7 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
                                                                  int64_t tiles_m, int64_t tiles_n,
                                                                  GemmEpilogue ep, GemmSecond sec) {
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
+  if (MODE == kGemmAccum && guard_tripped(ep)) return;   // the whole grid leaves together
   float* sc_row = reinterpret_cast<float*>(lds + kLdsScales);
   float* sc_col = sc_row + BM;
   // LDS byte address of the first stage (an address-space-3 pointer is a 32-bit offset)
@@ -318,19 +323,34 @@ bool gemm_persistent_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64
 // Compute units of the current device, looked up once per device (srq_create primes it, so
 // that no property query happens inside a caller's stream capture).
 hipError_t gemm_device_cus(int* cus) {
-  static int cached[64] = {0};
+  static std::atomic<int> cached[64];               // zero-initialised; a racing first query stores the same value
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= 64 || !cached[dev]) {
+  int n = (dev >= 0 && dev < 64) ? cached[dev].load(std::memory_order_relaxed) : 0;
+  if (!n) {
     hipDeviceProp_t prop;
     e = hipGetDeviceProperties(&prop, dev);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) { *cus = prop.multiProcessorCount; return hipSuccess; }
-    cached[dev] = prop.multiProcessorCount;
+    n = prop.multiProcessorCount;
+    if (dev >= 0 && dev < 64) cached[dev].store(n, std::memory_order_relaxed);
   }
-  *cus = cached[dev];
+  *cus = n;
   return hipSuccess;
+}
+
+hipError_t ensure_dynamic_lds(const void* kernel, int bytes) {
+  static std::mutex mu;
+  static std::vector<std::pair<int, const void*>> done;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const auto& d : done)
+    if (d.first == dev && d.second == kernel) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.emplace_back(dev, kernel);
+  return e;
 }
 
 hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
@@ -358,16 +378,8 @@ hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8
     kern = scale ? gemm_i8_persistent_kernel<kGemmAccum, false, true>
                  : gemm_i8_persistent_kernel<kGemmAccum, false, false>;
   }
-  static const void* attr_done[8] = {nullptr};
-  bool done = false;
-  for (const void* p : attr_done) done |= p == reinterpret_cast<const void*>(kern);
-  if (!done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    for (auto& p : attr_done)
-      if (!p) { p = reinterpret_cast<const void*>(kern); break; }
-  }
+  e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kLdsBytes);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), kLdsBytes, st, M, N, K, Qa, lda, Qb, ldb, tm, tn, ep,
                      sec);
   return hipGetLastError();

@@ -39,6 +39,7 @@ __global__ __launch_bounds__(256) void gemm_i8_sparse24_kernel(int64_t M, int64_
                                                                const int8_t* __restrict__ Qb, int64_t ldb,
                                                                int64_t tiles_m, int64_t tiles_n, GemmEpilogue ep) {
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
+  if (guard_tripped(ep)) return;                              // the whole grid leaves together
   float* sc_m = reinterpret_cast<float*>(lds + kLdsScales);   // scale of the sparse operand's vectors
   float* sc_n = sc_m + BM;                                    // scale of the dense operand's vectors
   const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) int8_t*)lds);
@@ -302,16 +303,8 @@ hipError_t launch_gemm_i8_sparse24(int64_t Mv, int64_t Nv, int64_t K, const int8
                GemmEpilogue);
   kern = trans ? (scale ? gemm_i8_sparse24_kernel<true, true> : gemm_i8_sparse24_kernel<true, false>)
                : (scale ? gemm_i8_sparse24_kernel<false, true> : gemm_i8_sparse24_kernel<false, false>);
-  static const void* attr_done[4] = {nullptr};
-  bool done = false;
-  for (const void* p : attr_done) done |= p == reinterpret_cast<const void*>(kern);
-  if (!done) {
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e2 != hipSuccess) return e2;
-    for (auto& p : attr_done)
-      if (!p) { p = reinterpret_cast<const void*>(kern); break; }
-  }
+  e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kLdsBytes);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), kLdsBytes, st, Mv, Nv, K, Av, An, Qb, ldb, tm, tn, ep);
   return hipGetLastError();
 }

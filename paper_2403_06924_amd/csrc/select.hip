@@ -193,13 +193,16 @@ __global__ __launch_bounds__(256) void densify_kernel(const int32_t* __restrict_
   for (int64_t p = p0 + threadIdx.x; p < p1; p += 256) row[idx[p]] = val[p];
 }
 
-__global__ void stats_kernel(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b,
-                             srq_stats_t* out) {
+__global__ void stats_kernel(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b, int64_t cap_a,
+                             int64_t cap_b, srq_stats_t* out) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
-    out->nnz_a = nnz_a ? *nnz_a : 0;
-    out->nnz_b = nnz_b ? *nnz_b : 0;
+    const int64_t na = nnz_a ? *nnz_a : 0, nb = nnz_b ? *nnz_b : 0;
+    out->nnz_a = na;
+    out->nnz_b = nb;
     out->path_a = path_a;
     out->path_b = path_b;
+    out->overflow = (na > cap_a ? 1 : 0) | (nb > cap_b ? 2 : 0);
+    out->reserved = 0;
   }
 }
 
@@ -289,9 +292,9 @@ hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* 
   return hipGetLastError();
 }
 
-hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b,
-                        srq_stats_t* out, hipStream_t st) {
-  hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(64), 0, st, nnz_a, nnz_b, path_a, path_b, out);
+hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b, int64_t cap_a,
+                        int64_t cap_b, srq_stats_t* out, hipStream_t st) {
+  hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(64), 0, st, nnz_a, nnz_b, path_a, path_b, cap_a, cap_b, out);
   return hipGetLastError();
 }
 

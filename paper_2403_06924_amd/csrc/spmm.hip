@@ -22,6 +22,7 @@ __global__ __launch_bounds__(64) void spmm_valu_kernel(int64_t nvec, int64_t nel
                                                        const int8_t* __restrict__ val, int64_t capacity,
                                                        const int8_t* __restrict__ R, int64_t ldr,
                                                        GemmEpilogue ep) {
+  if (guard_tripped(ep)) return;
   const int64_t v = blockIdx.y;
   const int64_t e0 = (int64_t)blockIdx.x * kBlockElems + threadIdx.x * kLaneElems;
   int64_t p0 = ptr[v], p1 = ptr_end[v];
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
   const int local = id >> 3;
   const int chunk = (local / nvb) * 8 + (id & 7);
   const int vb = local % nvb;
-  if (chunk >= nch) return;
+  if (chunk >= nch || guard_tripped(ep)) return;
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t e0 = (int64_t)chunk * E + lane * LE;

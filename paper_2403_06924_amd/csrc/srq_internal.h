@@ -47,7 +47,18 @@ struct GemmEpilogue {
   float alpha, beta;
   const float* Cin;
   int64_t ldcin;
+  // Overflow guard of the non-synchronising modes: when set, a kernel that adds a correction
+  // term (or applies alpha / beta after one) does nothing if the selection kept more entries
+  // than the compressed arrays hold (guard_nnz[0] > guard_cap_a or guard_nnz[1] > guard_cap_b),
+  // so that C stays the uncorrected first product instead of receiving a truncated correction.
+  const int64_t* guard_nnz;   // device int64[2]: kept entries of A' and B' (null: no guard)
+  int64_t guard_cap_a, guard_cap_b;
 };
+
+// true when the epilogue's overflow guard is set and tripped (wave-uniform: scalar loads)
+static __device__ __forceinline__ bool guard_tripped(const GemmEpilogue& ep) {
+  return ep.guard_nnz && (ep.guard_nnz[0] > ep.guard_cap_a || ep.guard_nnz[1] > ep.guard_cap_b);
+}
 
 // Second product of a paired accumulate-mode launch of the persistent kernel: C += dequant(Qa.Qb^T)
 // with its own scales, right after the first product of the same output tile (Qa == null: none).
@@ -176,6 +187,9 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int
                           const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st);
 // persistent-workgroup variant for full, aligned, large problems (chosen inside launch_gemm_i8)
 hipError_t gemm_device_cus(int* cus);
+// raises a kernel's dynamic-LDS limit to `bytes` once per (device, kernel); safe to call from
+// several host threads
+hipError_t ensure_dynamic_lds(const void* kernel, int bytes);
 bool gemm_persistent_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb,
                         int64_t ldb, const GemmEpilogue& ep);
 // (second: accumulate mode only; both products must pass gemm_persistent_ok)
@@ -207,8 +221,10 @@ hipError_t launch_gemm_i8_sparse24(int64_t Mv, int64_t Nv, int64_t K, const int8
                                    const int8_t* Qb, int64_t ldb, bool trans, const GemmEpilogue& ep,
                                    hipStream_t st);
 
-hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b,
-                        srq_stats_t* out, hipStream_t st);
+// (cap_a / cap_b: entries the compressed arrays of the operand hold; a larger count sets the
+// operand's bit in srq_stats_t::overflow)
+hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b, int64_t cap_a,
+                        int64_t cap_b, srq_stats_t* out, hipStream_t st);
 hipError_t launch_scale_only(int64_t M, int64_t N, const GemmEpilogue& ep, hipStream_t st);
 
 }  // namespace srq

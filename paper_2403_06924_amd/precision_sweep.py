@@ -31,17 +31,6 @@ def rel_err(torch, C64, C):
     return float(torch.linalg.norm(C64 - C.double()) / torch.linalg.norm(C64))
 
 
-def calibrate(torch, X, dvec, axis, density):
-    d = dvec.view(-1, 1) if axis == 0 else dvec.view(1, -1)
-    rho = (X.abs() / d).reshape(-1)
-    keep = int(round(rho.numel() * density))
-    if keep <= 0:
-        return float("inf")
-    if keep >= rho.numel():
-        return 0.0
-    return float(torch.sort(rho).values[rho.numel() - keep - 1].item())
-
-
 def sweep(size, seed, bits_list=(8, 4), kinds=KINDS, densities=DENSITIES, out=print):
     import torch
     from . import binding as b
@@ -71,7 +60,7 @@ def sweep(size, seed, bits_list=(8, 4), kinds=KINDS, densities=DENSITIES, out=pr
             _, _, drow, dcol = h.gemm_i8(Qa, sa, Qb, sb)
             cells = []
             for d in densities:
-                ta, tb = calibrate(torch, A, drow, 0, d), calibrate(torch, B, dcol, 1, d)
+                ta, tb = wl.theta_for_density(A, drow, 0, d), wl.theta_for_density(B, dcol, 1, d)
                 stats = b.stats_tensor()
                 C, _, _ = h.compensated_gemm(A, B, ta, tb, bits=bits, stats=stats)
                 torch.cuda.synchronize()
@@ -114,7 +103,7 @@ def qr_table(size, seed, bits_list=(8, 4), kinds=("chisquare", "uniform", "norma
             _, _, drow, dcol = h.gemm_i8(Qa, sa, Qb, sb)
             cells = []
             for d in densities:
-                ta, tb = calibrate(torch, Q, drow, 0, d), calibrate(torch, R, dcol, 1, d)
+                ta, tb = wl.theta_for_density(Q, drow, 0, d), wl.theta_for_density(R, dcol, 1, d)
                 C, _, _ = h.compensated_gemm(Q, R, ta, tb, bits=bits)
                 cells.append(rel_err(torch, X64, C))
             rows.append((kind, bits, e_fp32, e_origin, e_full, cells))

@@ -31,7 +31,6 @@ def timed(torch, fn, reps):
 def table(sizes, densities=DENSITIES, seed=11, out=print):
     import torch
     from . import binding as b
-    from .precision_sweep import calibrate
     if not torch.cuda.is_available():
         raise RuntimeError("speed_table needs a GPU")
     h = b.Srq(device=0)
@@ -50,7 +49,7 @@ def table(sizes, densities=DENSITIES, seed=11, out=print):
         del Qa, Qb
         cells = []
         for d in densities:
-            ta, tb = calibrate(torch, A, drow, 0, d), calibrate(torch, B, dcol, 1, d)
+            ta, tb = wl.theta_for_density(A, drow, 0, d), wl.theta_for_density(B, dcol, 1, d)
             md = min(1.0, 1.3 * d + 0.01)
             t = timed(torch, lambda: h.compensated_gemm(A, B, ta, tb, out=C, max_density=md), reps)
             cells.append(ops / t / 1e12)

@@ -120,15 +120,31 @@ def qr_factors(kind: str, n: int, seed: int):
     return X, np.ascontiguousarray(Q.astype(np.float32)), np.ascontiguousarray(R.astype(np.float32))
 
 
-def theta_for_density(X, dvec, axis: str, density: float) -> float:
+def theta_for_density(X, dvec, axis, density: float) -> float:
     """Harness-side calibration: the threshold factor theta such that about
     ``density`` of the entries of X satisfy |x| > theta * dvec[v].
 
     This is the (1-density)-quantile of |x| / dvec[v]; it is not part of the
-    method (the paper sweeps theta and reports the density it gets)."""
+    method (the paper sweeps theta and reports the density it gets).  X and dvec
+    are numpy arrays or torch tensors (the quantile is then taken on the tensor's
+    device); axis is "row" (or 0) when dvec holds one value per row of X, "col"
+    (or 1) for one per column.  The one copy of this helper: bench.py, the sweep
+    harnesses and the tests all call it."""
+    by_row = axis in ("row", 0)
+    if hasattr(X, "detach"):                            # torch tensors
+        import torch
+        d = dvec.view(-1, 1) if by_row else dvec.view(1, -1)
+        rho = (X.abs() / d).reshape(-1)
+        n = rho.numel()
+        keep = int(round(n * density))
+        if keep <= 0:
+            return float("inf")
+        if keep >= n:
+            return 0.0
+        return float(torch.sort(rho).values[n - keep - 1].item())   # a sort is far faster than kthvalue here
     X = np.asarray(X, dtype=np.float32)
     d = np.asarray(dvec, dtype=np.float32)
-    d = d.reshape(-1, 1) if axis == "row" else d.reshape(1, -1)
+    d = d.reshape(-1, 1) if by_row else d.reshape(1, -1)
     rho = (np.abs(X) / d).reshape(-1)
     keep = int(round(rho.size * density))
     if keep <= 0:

@@ -45,12 +45,7 @@ def gpu_thetas(srq, b, Ad, Bd, density):
     Qb, sb, _ = srq.quantize(Bd, b.AXIS_COL)
     _, _, drow, dcol = srq.gemm_i8(Qa, sa, Qb, sb)
 
-    def cal(X, d, axis):
-        dv = d.view(-1, 1) if axis == 0 else d.view(1, -1)
-        rho = (X.abs() / dv).reshape(-1)
-        keep = int(round(rho.numel() * density))
-        return float(torch.sort(rho).values[rho.numel() - keep - 1].item())
-    return cal(Ad, drow, 0), cal(Bd, dcol, 1)
+    return wl.theta_for_density(Ad, drow, 0, density), wl.theta_for_density(Bd, dcol, 1, density)
 
 
 @pytest.mark.parametrize("density", [0.01, 0.05, 0.20])
@@ -105,15 +100,20 @@ def test_c2_full_bounds(srq, b):
     assert torch.equal(Cd, C0)                                            # the dense branch gives the same
 
 
-def sampled_check(srq, b, name, density, nsample, seed):
+def sampled_check(srq, b, name, density, nsample, seed, strategy=None, bit_identical=True):
+    """Full-size parity on what the oracle can compute one by one: every element-wise stage and the
+    compressed selection of every vector in full; the INT32 products, the means and the final FP32
+    output C on `nsample` sampled rows and `nsample` sampled columns (C is NOT compared on the other
+    rows and columns at these sizes: the oracle's three integer products of a whole 8192^3 or 16384^3
+    problem do not fit a test's time)."""
     w = wl.WORKLOADS[name]
     M, N, K = w.M, w.N, w.K
     A, B = wl.make_inputs(name)
     Ad, Bd = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     ta, tb = gpu_thetas(srq, b, Ad, Bd, density)
     stats = b.stats_tensor()
-    Cd, _, _ = srq.compensated_gemm(Ad, Bd, ta, tb, strategy=b.STRATEGY_AUTO, stats=stats,
-                                    max_density=min(1.0, density * 1.25 + 0.01))
+    Cd, _, _ = srq.compensated_gemm(Ad, Bd, ta, tb, strategy=b.STRATEGY_AUTO if strategy is None else strategy,
+                                    stats=stats, max_density=min(1.0, density * 1.25 + 0.01))
     torch.cuda.synchronize()
     st = b.read_stats(stats)
     im = srq.intermediates(M, N, K)
@@ -160,7 +160,8 @@ def sampled_check(srq, b, name, density, nsample, seed):
     C_rows = (D_rows + T1) + T2
     got = host(Cd[torch.from_numpy(rows).cuda()])
     assert o.error_rel(C_rows, got) <= REL_TOL
-    assert (got == C_rows).mean() > 0.999            # in practice bit-identical
+    if bit_identical:
+        assert (got == C_rows).mean() > 0.999        # in practice bit-identical
     T1c = o.dequant_product(o.int_matmul(Ap, RB_int[:, cols]), s_a, s_rb[cols])
     T2c = o.dequant_product(o.int_matmul(RA_int, Bp[:, cols]), s_ra, s_b[cols])
     C_cols = (D_cols + T1c) + T2c
@@ -174,32 +175,19 @@ def test_c3_headline_sampled(srq, b):
     assert st["path_a"] in (1, 2) and st["path_b"] in (1, 2)
 
 
-def test_c3_structured_2to4_matches_matrix_core_path(srq, b):
-    """Full size, the launch configuration `bench.py --strategy smfmac` times: the 2:4 split + spill
-    execution of both terms against the plain matrix-core execution (which the test above checks
-    against the oracle).  The spilled part of a term is rounded into C separately, so the two agree
-    to rounding, not bit for bit."""
-    A, B = wl.make_inputs("C3")
-    Ad, Bd = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
-    ta, tb = gpu_thetas(srq, b, Ad, Bd, 0.05)
-    stats = b.stats_tensor()
-    C24, _, _ = srq.compensated_gemm(Ad, Bd, ta, tb, strategy=b.STRATEGY_CSR_SMFMAC, stats=stats, max_density=0.08)
-    torch.cuda.synchronize()
-    st = b.read_stats(stats)
+def test_c3_structured_2to4_sampled(srq, b):
+    """Full size, the launch configuration `bench.py --strategy smfmac` times: the 2:4 execution of
+    both correction terms against the oracle on sampled rows and columns (codes, scales, compressed
+    selection of every vector in full, as for the other strategies)."""
+    st = sampled_check(srq, b, "C3", 0.05, 192, seed=11, strategy=b.STRATEGY_CSR_SMFMAC, bit_identical=False)
     assert st["path_a"] == 4 and st["path_b"] == 4
-    C24 = C24.clone()
-    C2, _, _ = srq.compensated_gemm(Ad, Bd, ta, tb, strategy=b.STRATEGY_CSR_MFMA, max_density=0.08)
-    torch.cuda.synchronize()
-    diff = (C24.double() - C2.double()).norm() / C2.double().norm()
-    assert float(diff) <= 1e-6
-    assert float((C24 == C2).float().mean()) > 0.5      # rows and columns without spilled entries agree exactly
 
 
 def test_c4_rectangular_sampled(srq, b):
     sampled_check(srq, b, "C4", 0.02, 128, seed=12)
 
 
-@pytest.mark.parametrize("density", [0.05, 0.50])
+@pytest.mark.parametrize("density", [0.05, 0.20, 0.50])
 def test_c5_wide_range_sampled(srq, b, density):
     sampled_check(srq, b, "C5", density, 48, seed=13)
 

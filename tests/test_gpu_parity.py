@@ -430,6 +430,38 @@ def test_capacity_status_in_synchronising_mode(srq, b):
         srq.ws = None
 
 
+@pytest.mark.parametrize("strategy", [1, 2, 3])
+@pytest.mark.parametrize("shape", [(128, 128, 256), (2048, 2048, 256)])
+def test_overflow_in_non_synchronising_modes(srq, b, strategy, shape):
+    """A fixed strategy cannot read the counts on the host.  With a workspace sized for 1 % and a
+    selection that keeps everything, every execution must leave C = D_F (no correction from
+    truncated arrays), say so in the statistics, and still report the true counts; the same call
+    with enough room then gives the oracle's result (the guard does not trip by mistake).
+    The larger shape takes the persistent matrix-core kernels."""
+    M, N, K = shape
+    A, B = wl.make_inputs("C2", M, N, K)
+    plain = o.quantized_product(A, B)
+    srq.ws = None                                              # force a workspace sized for 1 % density
+    try:
+        stats = b.stats_tensor()
+        C, _, _ = srq.compensated_gemm(dev(A), dev(B), 0.0, 0.0, strategy=strategy, max_density=0.01,
+                                       stats=stats, alpha=0.5)
+        torch.cuda.synchronize()
+        assert srq.last_status == b.OK
+        st = b.read_stats(stats)
+        assert st["overflow"] == 3
+        assert st["nnz_a"] == int((A != 0).sum()) and st["nnz_b"] == int((B != 0).sum())
+        assert (host(C) == plain.D_F).all()                    # uncorrected, alpha not applied
+    finally:
+        srq.ws = None
+    stats = b.stats_tensor()
+    C, _, _ = srq.compensated_gemm(dev(A), dev(B), 0.0, 0.0, strategy=strategy, stats=stats, alpha=0.5)
+    torch.cuda.synchronize()
+    assert b.read_stats(stats)["overflow"] == 0
+    ref = o.compensated_gemm(A, B, 0.0, alpha=0.5)
+    assert o.error_rel(ref.C, host(C)) <= REL_TOL
+
+
 def test_run_twice_is_deterministic(srq, b):
     A, B = wl.make_inputs("C3", 300, 260, 512)
     Ad, Bd = dev(A), dev(B)
