@@ -214,6 +214,26 @@ srq_status_t srq_gemm_i8(srq_handle_t handle, int64_t M, int64_t N, int64_t K, c
                          const float* sa, const int8_t* Qb, int64_t ldb, const float* sb, float* D_F,
                          int32_t* D_int, int64_t ldd, float* drow, float* dcol, void* stream);
 
+/* srq_gemm_i8 for callers that cannot hand the library any memory of their own and may not
+ * allocate: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same results bit for bit; the handle's workspace is neither needed nor touched.
+ * The partial sums of |D_F| (the only scratch memory the call needs, and only when drow / dcol are
+ * given) go to a fixed array inside the library's code object, srq_static_scratch_bytes() bytes
+ * (8 MiB) per GPU, held from the moment the library is loaded on that GPU until the process ends.
+ * Limit: 8 * (ceil(N/128) * M + ceil(M/128) * N), each term rounded up to 256, must not exceed that
+ * size (e.g. M = N = 8192, or 4096 x 14336); a larger problem is refused with
+ * SRQ_STATUS_WORKSPACE before anything is launched.  The call allocates and frees nothing and
+ * records no memset.  All calls on one GPU share that GPU's array: calls that overlap in time on
+ * the same GPU (two streams, two threads) race and must be serialised by the caller; calls one
+ * after the other need no clearing in between (every slot read was written by the same call).
+ * Returns SRQ_STATUS_HIP_ERROR if the array's address could not be obtained when the handle was
+ * created. */
+srq_status_t srq_gemm_i8_static_scratch(srq_handle_t handle, int64_t M, int64_t N, int64_t K, const int8_t* Qa,
+                                        int64_t lda, const float* sa, const int8_t* Qb, int64_t ldb,
+                                        const float* sb, float* D_F, int32_t* D_int, int64_t ldd, float* drow,
+                                        float* dcol, void* stream);
+size_t srq_static_scratch_bytes(void);
+
 /* C[i,j] += fl(fl(float(DR[i,j])) * fl(s_row[i]*s_col[j])) with DR the product of a
  * compressed operand and dense residual codes:
  *   side = SRQ_AXIS_ROW: DR = A'.RB, (ptr,idx,val) = CSR of A' (M vectors over K), Rq = RB codes;

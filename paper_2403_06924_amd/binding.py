@@ -27,6 +27,7 @@ EXPORTS = [
     "srq_stage_workspace_bytes", "srq_last_hip_error", "srq_status_string", "srq_quantize",
     "srq_build_sparse_residual", "srq_gemm_i8", "srq_spmm_accumulate", "srq_compensated_gemm",
     "srq_get_intermediates", "srq_profile_enable", "srq_profile_read", "srq_set_scale_mode",
+    "srq_gemm_i8_static_scratch", "srq_static_scratch_bytes",
 ]
 STAGES = ["quantize", "gemm", "select", "residual", "term1_prep", "term1", "term2_prep", "term2"]
 
@@ -81,6 +82,8 @@ def load():
     lib.srq_build_sparse_residual.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, vp, i32, i32, vp, i64, i32,
                                               vp, vp, vp, vp, i64, vp, vp]
     lib.srq_gemm_i8.argtypes = [vp, i64, i64, i64, vp, i64, vp, vp, i64, vp, vp, vp, i64, vp, vp, vp]
+    lib.srq_gemm_i8_static_scratch.argtypes = lib.srq_gemm_i8.argtypes
+    lib.srq_static_scratch_bytes.argtypes = []
     lib.srq_spmm_accumulate.argtypes = [vp, i32, i32, i64, i64, i64, vp, vp, vp, vp, i64, vp, vp, vp, vp, i64, vp]
     lib.srq_compensated_gemm.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, f32, f32, i32, i32, f32, i32,
                                          f32, f32, vp, i64, vp, i64, vp, C.POINTER(Debug), vp]
@@ -89,8 +92,9 @@ def load():
     lib.srq_set_scale_mode.argtypes = [vp, i32]
     lib.srq_profile_read.argtypes = [vp, C.POINTER(f32)]
     for name in EXPORTS:
-        if name != "srq_status_string":
+        if name not in ("srq_status_string", "srq_static_scratch_bytes"):
             getattr(lib, name).restype = i32
+    lib.srq_static_scratch_bytes.restype = sz
     _lib = lib
     return lib
 
@@ -236,21 +240,29 @@ class Srq:
         out.update(Rq=Rq, rscale=rscale, ptr=ptr, idx=idx, val=val, nnz=nnz)
         return out
 
-    def gemm_i8(self, Qa, sa, Qb, sb, want_int=False, want_means=True):
-        """srq_gemm_i8 on vector-major code matrices Qa[M,K], Qb[N,K]."""
+    def gemm_i8(self, Qa, sa, Qb, sb, want_int=False, want_means=True, static_scratch=False, out=None):
+        """srq_gemm_i8 on vector-major code matrices Qa[M,K], Qb[N,K]; with static_scratch=True
+        srq_gemm_i8_static_scratch (no workspace is attached or used; `out` = (D_F, drow, dcol)
+        lets the caller pass every output, so that the call itself allocates nothing)."""
         import torch
         M, K = Qa.shape
         N = Qb.shape[0]
         dev = Qa.device
-        self.ensure_workspace(stage_workspace_bytes(max(M, 1), max(N, 1), max(K, 1)))
-        D_F = torch.empty((M, N), dtype=torch.float32, device=dev)
+        if not static_scratch:
+            self.ensure_workspace(stage_workspace_bytes(max(M, 1), max(N, 1), max(K, 1)))
         D_int = torch.empty((M, N), dtype=torch.int32, device=dev) if want_int else None
-        drow = torch.empty(M, dtype=torch.float32, device=dev) if want_means else None
-        dcol = torch.empty(N, dtype=torch.float32, device=dev) if want_means else None
-        st = self.lib.srq_gemm_i8(self.h, M, N, K, _ptr(Qa), Qa.stride(0) if M else K, _ptr(sa), _ptr(Qb),
-                                  Qb.stride(0) if N else K, _ptr(sb), _ptr(D_F), _ptr(D_int), N, _ptr(drow),
-                                  _ptr(dcol), self._stream())
-        self._ret(st, "srq_gemm_i8")
+        if out is not None:
+            D_F, drow, dcol = out
+        else:
+            D_F = torch.empty((M, N), dtype=torch.float32, device=dev)
+            drow = torch.empty(M, dtype=torch.float32, device=dev) if want_means else None
+            dcol = torch.empty(N, dtype=torch.float32, device=dev) if want_means else None
+        fn = self.lib.srq_gemm_i8_static_scratch if static_scratch else self.lib.srq_gemm_i8
+        st = fn(self.h, M, N, K, _ptr(Qa), Qa.stride(0) if M else K, _ptr(sa), _ptr(Qb),
+                Qb.stride(0) if N else K, _ptr(sb), _ptr(D_F), _ptr(D_int), N, _ptr(drow),
+                _ptr(dcol), self._stream())
+        self._ret(st, "srq_gemm_i8_static_scratch" if static_scratch else "srq_gemm_i8")
+        self.last_status = st
         return D_F, D_int, drow, dcol
 
     def spmm_accumulate(self, side, strategy, M, N, K, ptr, idx, val, Rq, s_row, s_col, C_out, want_int=False):

@@ -2,6 +2,7 @@
 // Algorithm 1.  No device memory is allocated here; everything lives in the caller's
 // workspace.
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <string.h>
 
@@ -9,7 +10,39 @@
 
 using namespace srq;
 
+// Scratch memory of the one entry point that may not use a caller's workspace
+// (srq_gemm_i8_static_scratch): a fixed array in the code object, one copy per GPU the library is
+// loaded on, holding the partial sums of |D_F| between the product and the kernel that turns them
+// into means.  Every call on a GPU shares that GPU's copy; every slot a call reads it has written
+// before, so nothing has to be cleared between calls.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+// The array's name is only a host-side handle; its device address differs per GPU and is looked up
+// once per device (srq_create, with that device current) with hipGetSymbolAddress.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+char* g_scratch_ptr[kMaxDevices] = {nullptr};
+hipError_t g_scratch_error = hipSuccess;
+
+hipError_t prime_static_scratch(int device) {      // the device is current
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[device]) return hipSuccess;
+  void* ptr = nullptr;
+  hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) { g_scratch_error = e; return e; }
+  g_scratch_ptr[device] = static_cast<char*>(ptr);
+  return hipSuccess;
+}
+
+char* static_scratch_of(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  return g_scratch_ptr[device];
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -233,6 +266,8 @@ srq_status_t srq_create(srq_handle_t* handle, int device) {
     int cus = 0;
     if (e == hipSuccess) e = srq::gemm_device_cus(&cus);
     if (e != hipSuccess) { delete c; return SRQ_STATUS_HIP_ERROR; }
+    // (a failure here only disables srq_gemm_i8_static_scratch, which then reports it)
+    c->last_hip_error = (int)prime_static_scratch(device);
   }
   *handle = c;
   return SRQ_STATUS_OK;
@@ -431,9 +466,12 @@ srq_status_t srq_build_sparse_residual(srq_handle_t h, const float* X, int64_t r
 }
 
 // ------------------------------------------------------------------------------------------
-srq_status_t srq_gemm_i8(srq_handle_t h, int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
-                         const float* sa, const int8_t* Qb, int64_t ldb, const float* sb, float* D_F,
-                         int32_t* D_int, int64_t ldd, float* drow, float* dcol, void* stream) {
+// The first product with its means; `scratch` = where the partial sums of |D_F| go: the handle's
+// workspace (use_static false) or this device's copy of the library's static scratch array.
+static srq_status_t gemm_i8_impl(srq_handle_t h, int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
+                                 const float* sa, const int8_t* Qb, int64_t ldb, const float* sb, float* D_F,
+                                 int32_t* D_int, int64_t ldd, float* drow, float* dcol, void* stream,
+                                 bool use_static) {
   if (!h) return SRQ_STATUS_INVALID_ARG;
   if (M < 0 || N < 0 || K < 0) return SRQ_STATUS_INVALID_ARG;
   if (k_overflows(K, 128)) return SRQ_STATUS_K_OVERFLOW;     // codes may use the full int8 range
@@ -443,7 +481,10 @@ srq_status_t srq_gemm_i8(srq_handle_t h, int64_t M, int64_t N, int64_t K, const 
   }
   if ((drow == nullptr) != (dcol == nullptr)) return SRQ_STATUS_INVALID_ARG;
   size_t need = align_up((size_t)tiles(N, gemm_tile_n()) * M * 8) + align_up((size_t)tiles(M, gemm_tile_m()) * N * 8);
-  if (drow && M > 0 && N > 0 && (!h->ws || h->ws_bytes < need)) return SRQ_STATUS_WORKSPACE;
+  if (drow && M > 0 && N > 0) {
+    // (a problem whose partial sums do not fit is refused before anything is launched)
+    if (use_static ? need > kStaticScratchBytes : (!h->ws || h->ws_bytes < need)) return SRQ_STATUS_WORKSPACE;
+  }
   srq_status_t s = bind_device(h);
   if (s) return s;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -454,7 +495,13 @@ srq_status_t srq_gemm_i8(srq_handle_t h, int64_t M, int64_t N, int64_t K, const 
   ep.s_row = sa; ep.s_col = sb; ep.C = D_F; ep.ldc = ldd; ep.D_int = D_int; ep.ldd = ldd;
   ep.alpha = 1.f;
   if (drow) {
-    Carver c{reinterpret_cast<char*>(h->ws), 0};
+    char* base = reinterpret_cast<char*>(h->ws);
+    if (use_static) {
+      base = static_scratch_of(h->device);
+      // (no address: the lookup at srq_create failed, or the device number is out of range)
+      if (!base) return hip_fail(h, g_scratch_error != hipSuccess ? g_scratch_error : hipErrorInvalidDevice);
+    }
+    Carver c{base, 0};
     ep.row_part = c.take<double>((size_t)tiles(N, gemm_tile_n()) * M);
     ep.col_part = c.take<double>((size_t)tiles(M, gemm_tile_m()) * N);
   }
@@ -467,6 +514,21 @@ srq_status_t srq_gemm_i8(srq_handle_t h, int64_t M, int64_t N, int64_t K, const 
   }
   return SRQ_STATUS_OK;
 }
+
+srq_status_t srq_gemm_i8(srq_handle_t h, int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
+                         const float* sa, const int8_t* Qb, int64_t ldb, const float* sb, float* D_F,
+                         int32_t* D_int, int64_t ldd, float* drow, float* dcol, void* stream) {
+  return gemm_i8_impl(h, M, N, K, Qa, lda, sa, Qb, ldb, sb, D_F, D_int, ldd, drow, dcol, stream, false);
+}
+
+srq_status_t srq_gemm_i8_static_scratch(srq_handle_t h, int64_t M, int64_t N, int64_t K, const int8_t* Qa,
+                                        int64_t lda, const float* sa, const int8_t* Qb, int64_t ldb,
+                                        const float* sb, float* D_F, int32_t* D_int, int64_t ldd, float* drow,
+                                        float* dcol, void* stream) {
+  return gemm_i8_impl(h, M, N, K, Qa, lda, sa, Qb, ldb, sb, D_F, D_int, ldd, drow, dcol, stream, true);
+}
+
+size_t srq_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 // ------------------------------------------------------------------------------------------
 srq_status_t srq_spmm_accumulate(srq_handle_t h, srq_axis_t side, srq_strategy_t strategy, int64_t M,
