@@ -148,6 +148,19 @@ def test_staged_entry_points_validation(dry):
     assert g(drow=None) == b.INVALID_ARG                       # means come as a pair
     assert g(drow=None, dcol=None) == b.NO_DEVICE
     assert g(K=200000, lda=200000) == b.K_OVERFLOW
+    # the variant on the library's static scratch array: same validation, no workspace needed, and a
+    # problem whose partial sums exceed the array is refused before the device is even looked at
+    lib.srq_set_workspace(h, None, 0)
+    gs = lambda **kw: lib.srq_gemm_i8_static_scratch(h, kw.get("M", 64), kw.get("N", 64), 64, FAKE, 64, FAKE, FAKE,
+                                                     64, FAKE, kw.get("D", FAKE), None, kw.get("N", 64),
+                                                     kw.get("drow", FAKE), kw.get("dcol", FAKE), None)
+    assert g() == b.WORKSPACE and gs() == b.NO_DEVICE
+    assert gs(D=None) == b.INVALID_ARG
+    assert lib.srq_static_scratch_bytes() == 8 << 20
+    assert gs(M=8192, N=8192) == b.NO_DEVICE                   # exactly fills the array
+    assert gs(M=8192, N=8192 + 128) == b.WORKSPACE
+    assert gs(M=1 << 20, N=1 << 20, drow=None, dcol=None) == b.NO_DEVICE   # no means, no scratch
+    assert lib.srq_set_workspace(h, C.c_void_p(0x10000), b.stage_workspace_bytes(64, 64, 64)) == b.OK
     sp = lambda **kw: lib.srq_spmm_accumulate(h, kw.get("side", 0), kw.get("strat", b.STRATEGY_CSR_VALU), 64, 64,
                                               64, kw.get("ptr", FAKE), FAKE, FAKE, FAKE, kw.get("ldr", 64), FAKE,
                                               FAKE, FAKE, None, 64, None)
