@@ -77,9 +77,42 @@ def sweep(size, seed, bits_list=(8, 4), kinds=KINDS, densities=DENSITIES, out=pr
     return rows
 
 
+def qr_driver_table(size, seed, bits_list=(8, 4), kinds=("chisquare", "uniform", "normal", "exponential"),
+                    densities=(0.05, 0.2, 0.5), block=64, out=print):
+    """The QR experiment of Sec. 4.2 in the form of its table: a blocked Householder QR
+    (qr.householder_qr) whose trailing updates, accumulation of Q and final Q.R all run through
+    srq_compensated_gemm, E = ||X - Q.R||_F / ||X||_F per distribution, bit width and method
+    (origin = direct quantization, full = unreduced compensation, sparse at the given densities)."""
+    import torch
+    from . import binding as b
+    from . import qr
+    h = b.Srq(device=0)
+    rows = []
+    out("\n### Householder QR (block %d) with every large product through the library, %d x %d, seed %d: "
+        "E = ||X - Q.R||_F / ||X||_F\n" % (block, size, size, seed))
+    out("| distribution | bits | FP32 | origin | full | " + " | ".join("d=%.2f" % d for d in densities) + " |")
+    out("|---|---|---|---|---|" + "---|" * len(densities))
+    for kind in kinds:
+        X = torch.from_numpy(wl.paper_distribution(kind, (size, size), seed)).cuda()
+        X64 = X.double()
+        Q, R = qr.householder_qr(X, block=block)
+        e_fp32 = rel_err(torch, X64, Q @ R)
+        for bits in bits_list:
+            cells = []
+            for mm in ([qr.LibraryMatmul(h, "origin", bits), qr.LibraryMatmul(h, "full", bits)] +
+                       [qr.LibraryMatmul(h, "sparse", bits, density=d) for d in densities]):
+                Q, R = qr.householder_qr(X, mm, block=block)
+                cells.append(rel_err(torch, X64, mm(Q, R)))
+            rows.append((kind, bits, e_fp32, cells))
+            out("| %s | %d | %.2e | %s |" % (kind, bits, e_fp32, " | ".join("%.2e" % c for c in cells)))
+    h.close()
+    return rows
+
+
 def qr_table(size, seed, bits_list=(8, 4), kinds=("chisquare", "uniform", "normal", "exponential"),
              densities=(0.05, 0.2, 0.5), out=print):
-    """The QR experiment of Sec. 4.2: Q.R by the quantized products against the factored matrix."""
+    """The last product of the QR experiment alone: Q.R of finished (numpy) Householder factors by
+    the quantized products against the factored matrix."""
     import torch
     from . import binding as b
     h = b.Srq(device=0)
@@ -117,10 +150,16 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--size", type=int, default=1024)
     ap.add_argument("--seed", type=int, default=7)
-    ap.add_argument("--qr", action="store_true", help="also run the Q.R experiment of Sec. 4.2")
+    ap.add_argument("--qr", action="store_true",
+                    help="also run the QR experiment of Sec. 4.2 (blocked Householder QR through the library)")
+    ap.add_argument("--qr-factors", action="store_true", help="also multiply finished QR factors (last product only)")
+    ap.add_argument("--only-qr", action="store_true", help="skip the precision sweep")
     args = ap.parse_args()
-    sweep(args.size, args.seed)
-    if args.qr:
+    if not args.only_qr:
+        sweep(args.size, args.seed)
+    if args.qr or args.only_qr:
+        qr_driver_table(args.size, args.seed)
+    if args.qr_factors:
         qr_table(args.size, args.seed)
 
 
