@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3", help="C1..C5 (default C3: 8192^3 with outliers)")
     ap.add_argument("--density", type=float, default=None, help="target density of A' and B'")
-    ap.add_argument("--strategy", default="auto", choices=["auto", "valu", "mfma", "smfmac"])
+    ap.add_argument("--strategy", default="auto", choices=["auto", "valu", "mfma", "smfmac", "colblock"])
     ap.add_argument("--dense-fallback", type=float, default=2.0, help="Algorithm 1's limit s (>1: off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
@@ -126,7 +126,7 @@ def main():
     torch.cuda.empty_cache()
 
     strategy = {"auto": b.STRATEGY_AUTO, "valu": b.STRATEGY_CSR_VALU, "mfma": b.STRATEGY_CSR_MFMA,
-                "smfmac": b.STRATEGY_CSR_SMFMAC}[args.strategy]
+                "smfmac": b.STRATEGY_CSR_SMFMAC, "colblock": b.STRATEGY_COLBLOCK}[args.strategy]
     stats = b.stats_tensor()
     Cd = torch.empty((M, N), dtype=torch.float32, device="cuda")
     max_density = min(1.0, density * 1.25 + 0.01)
@@ -189,6 +189,9 @@ def main():
         elif path == 1:
             issued += own
             units.add("valu")
+        elif path == 5:                      # dense strip of one K-tile on the matrix cores + CSR remainder
+            issued += own + 2.0 * M * N * 128
+            units.update(("mfma", "valu"))
     corr = None
     if corr_ms > 0:
         on_valu = units == {"valu"}

@@ -64,11 +64,18 @@ typedef enum srq_strategy_t {
   SRQ_STRATEGY_AUTO = 0,        /* pick per term from the measured density (synchronises)   */
   SRQ_STRATEGY_CSR_VALU = 1,    /* row-wise CSR x dense on the vector ALUs                   */
   SRQ_STRATEGY_CSR_MFMA = 2,    /* CSR expanded to zero-filled INT8 tiles, matrix cores      */
-  SRQ_STRATEGY_CSR_SMFMAC = 3   /* expansion split into a 2:4 operand for the sparse matrix-   */
+  SRQ_STRATEGY_CSR_SMFMAC = 3,  /* expansion split into a 2:4 operand for the sparse matrix-   */
                                 /* core instruction + a spill list on the vector ALUs (needs */
                                 /* M, N multiples of 256; otherwise runs as CSR_MFMA).  The   */
                                 /* spilled part of a term is added to C separately, so C is  */
                                 /* within rounding of, not bit-identical to, the other paths  */
+  SRQ_STRATEGY_COLBLOCK = 4     /* column-block split: the indices k kept in at least 90 % of */
+                                /* an operand's vectors (up to 128 of them: whole outlier     */
+                                /* columns) form a dense strip that runs on the matrix cores; */
+                                /* the remaining entries run as CSR on the vector ALUs.  The  */
+                                /* two parts are added to C one after the other, so C is      */
+                                /* within rounding of the other paths; the INT32 sums are the */
+                                /* same                                                        */
 } srq_strategy_t;
 
 /* Granularity of the first-level scales in srq_compensated_gemm.  VECTOR is the method of
@@ -84,7 +91,8 @@ typedef struct srq_stats_t {
   int64_t nnz_a;        /* entries kept in A' (Algorithm 1, getSparsity)                    */
   int64_t nnz_b;        /* entries kept in B'                                               */
   int32_t path_a;       /* 0 = term skipped (theta = inf), 1 = CSR_VALU, 2 = CSR_MFMA,      */
-  int32_t path_b;       /* 3 = dense branch on the unreduced operand, 4 = CSR_SMFMAC        */
+  int32_t path_b;       /* 3 = dense branch on the unreduced operand, 4 = CSR_SMFMAC,       */
+                        /* 5 = COLBLOCK                                                     */
   int32_t overflow;     /* bit 0: A' kept more entries than the workspace's compressed      */
                         /* arrays hold, bit 1: the same for B'.  Non-zero means that NO      */
                         /* correction term was added: C holds the uncorrected first product  */

@@ -19,7 +19,7 @@ OK, INVALID_ARG, UNSUPPORTED, K_OVERFLOW, CAPACITY, WORKSPACE, HIP_ERROR, NO_DEV
 AXIS_ROW, AXIS_COL = 0, 1
 LAYOUT_VECTOR_MAJOR, LAYOUT_ELEMENT_MAJOR = 0, 1
 ROUND_NEAREST_EVEN, ROUND_TRUNC = 0, 1
-STRATEGY_AUTO, STRATEGY_CSR_VALU, STRATEGY_CSR_MFMA, STRATEGY_CSR_SMFMAC = 0, 1, 2, 3
+STRATEGY_AUTO, STRATEGY_CSR_VALU, STRATEGY_CSR_MFMA, STRATEGY_CSR_SMFMAC, STRATEGY_COLBLOCK = 0, 1, 2, 3, 4
 SCALE_VECTOR, SCALE_GLOBAL = 0, 1
 
 EXPORTS = [

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsrq.so")
 SOURCES = ["api.hip", "quantize.hip", "fused.hip", "select.hip", "gemm.hip", "gemm_persistent.hip",
-           "gemm_sparse24.hip", "sparse24.hip", "spmm.hip"]
+           "gemm_sparse24.hip", "sparse24.hip", "spmm.hip", "colblock.hip"]
 
 # -ffp-contract=off: the dequantize / residual steps are defined with one rounding per
 # operation, so no multiply-add may be fused.  Packed FP32 instructions stay off.

@@ -55,10 +55,19 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // operand on the matrix cores takes 0.49-0.58 ms at any density.  The same crossovers (1.3-1.5 %
 // and 0.75 %) were measured at 2048^3 and 4096^3.
 // execution of a correction term as reported in srq_stats_t (0: term skipped)
-constexpr int kPathValu = 1, kPathMfma = 2, kPathDense = 3, kPath24 = 4;
+constexpr int kPathValu = 1, kPathMfma = 2, kPathDense = 3, kPath24 = 4, kPathColblock = 5;
 inline int strategy_path(srq_strategy_t s) {
-  return s == SRQ_STRATEGY_CSR_VALU ? kPathValu : s == SRQ_STRATEGY_CSR_SMFMAC ? kPath24 : kPathMfma;
+  return s == SRQ_STRATEGY_CSR_VALU ? kPathValu : s == SRQ_STRATEGY_CSR_SMFMAC ? kPath24
+       : s == SRQ_STRATEGY_COLBLOCK ? kPathColblock : kPathMfma;
 }
+// which layouts of the OTHER operand's residual codes an execution reads: k-major for the vector
+// ALUs (also the spill of the 2:4 split and the remainder of the column-block split),
+// K-contiguous for the matrix cores
+inline bool path_reads_em(int path) { return path == kPathValu || path == kPath24 || path == kPathColblock; }
+inline bool path_reads_vm(int path) { return path >= kPathMfma; }
+
+// share of an operand's vectors that must keep an index k for k to join the dense strip
+constexpr double kColblockKeepRatio = 0.9;
 
 constexpr int64_t kNoCap = INT64_MAX;     // capacity of an operand that is not compacted
 
@@ -97,6 +106,10 @@ struct Plan {
   int8_t *sa_val, *sb_val;
   unsigned long long* sp_total;   // [2]
   int64_t cap_sa, cap_sb;
+  // column-block split: per-k counts, the strip's k list and flag bitmap, strips of both operands
+  int32_t *kcnt, *klist_a, *klist_b, *nstrip;   // kcnt is shared by the two operands (used one after the other)
+  uint32_t *kflag_a, *kflag_b;
+  int8_t *strip_a, *strip_rb, *strip_b, *strip_ra;
   size_t fixed_bytes;
 };
 
@@ -144,6 +157,12 @@ size_t plan_fixed(char* base, int64_t M, int64_t N, int64_t K, Plan* p) {
   p->sa_begin = c.take<int32_t>(M); p->sa_end = c.take<int32_t>(M);
   p->sb_begin = c.take<int32_t>(N); p->sb_end = c.take<int32_t>(N);
   p->sp_total = c.take<unsigned long long>(2);
+  p->kcnt = c.take<int32_t>((size_t)mask_words(K) * 64);
+  p->klist_a = c.take<int32_t>(kStripK); p->klist_b = c.take<int32_t>(kStripK);
+  p->nstrip = c.take<int32_t>(2);
+  p->kflag_a = c.take<uint32_t>((size_t)mask_words(K) * 2); p->kflag_b = c.take<uint32_t>((size_t)mask_words(K) * 2);
+  p->strip_a = c.take<int8_t>((size_t)M * kStripK); p->strip_rb = c.take<int8_t>((size_t)N * kStripK);
+  p->strip_b = c.take<int8_t>((size_t)N * kStripK); p->strip_ra = c.take<int8_t>((size_t)M * kStripK);
   p->fixed_bytes = c.off;
   return c.off;
 }
@@ -588,7 +607,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   if (M < 0 || N < 0 || K < 0) return SRQ_STATUS_INVALID_ARG;
   if (round != SRQ_ROUND_NEAREST_EVEN && round != SRQ_ROUND_TRUNC) return SRQ_STATUS_INVALID_ARG;
   if (strategy != SRQ_STRATEGY_AUTO && strategy != SRQ_STRATEGY_CSR_VALU && strategy != SRQ_STRATEGY_CSR_MFMA &&
-      strategy != SRQ_STRATEGY_CSR_SMFMAC)
+      strategy != SRQ_STRATEGY_CSR_SMFMAC && strategy != SRQ_STRATEGY_COLBLOCK)
     return SRQ_STATUS_INVALID_ARG;
   if (isnan(theta_a) || isnan(theta_b) || theta_a < 0.f || theta_b < 0.f) return SRQ_STATUS_INVALID_ARG;
   if (isnan(dense_fallback_density) || isnan(alpha) || isnan(beta)) return SRQ_STATUS_INVALID_ARG;
@@ -686,8 +705,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       // a wrong guess only costs that second pass)
       // (the 2:4 path reads both: K-contiguous codes on the matrix cores, k-major ones for its spill)
       const int expect_a = strategy == SRQ_STRATEGY_AUTO ? h->last_path_a : strategy_path(strategy);
-      const bool want_em = term_a && dense_fallback_density > 1.f && (expect_a == kPathValu || expect_a == kPath24);
-      const bool want_vm = !want_em || expect_a == kPath24;
+      const bool want_em = term_a && dense_fallback_density > 1.f && path_reads_em(expect_a);
+      const bool want_vm = !want_em || path_reads_vm(expect_a);
       // when B's selection pass will run it writes these codes too (one read of B less)
       rb_in_select = term_b;
       rb_want_em = want_em;
@@ -750,7 +769,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       // codes that execution reads: one read of A less
       const int expect_b = strategy == SRQ_STRATEGY_AUTO ? h->last_path_b : strategy_path(strategy);
       const bool want_ra_em = term_b && dense_fallback_density > 1.f &&
-                              (expect_b == kPathValu || expect_b == kPath24) &&
+                              path_reads_em(expect_b) &&
                               rows_mask_resid_em_ok(A, M, K, lda, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M, p.t_a);
       if (want_ra_em) {
         SRQ_HIP(h, launch_rows_mask_resid_em(A, M, K, lda, qmax, trunc, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M,
@@ -817,6 +836,14 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       path_b = kPathMfma;
     if (path_a == kPath24 || path_b == kPath24)
       SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.sp_total), 4, 0, st));   // spill counters
+    // the column-block split reads the keep-mask, which B's generic (unaligned) selection does not
+    // produce: such a term runs as plain CSR on the vector ALUs
+    if (path_b == kPathColblock && !fastB) path_b = kPathValu;
+    if (path_a == kPathColblock)
+      SRQ_HIP(h, launch_colblock_pick(p.mask_a, M, K, kColblockKeepRatio, p.kcnt, p.klist_a, p.kflag_a, p.nstrip, st));
+    if (path_b == kPathColblock)
+      SRQ_HIP(h, launch_colblock_pick(p.mask_b, N, K, kColblockKeepRatio, p.kcnt, p.klist_b, p.kflag_b, p.nstrip + 1,
+                                      st));
     // compaction to CSR of A' / CSC of B'; a term that will run on the matrix cores also gets
     // its operand expanded to zero-filled dense codes in the same pass
     // (the dense branch multiplies the unreduced codes: its operand is counted, not compacted)
@@ -845,8 +872,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     }
     // lines 4-6: residual matrices and their codes, in the layouts the chosen paths read
     // (RA feeds term 2, RB feeds term 1)
-    bool ra_vm = path_b >= 2, ra_em = path_b == kPathValu || path_b == kPath24;
-    bool rb_vm = path_a >= 2, rb_em = path_a == kPathValu || path_a == kPath24;
+    bool ra_vm = path_reads_vm(path_b), ra_em = path_reads_em(path_b);
+    bool rb_vm = path_reads_vm(path_a), rb_em = path_reads_em(path_a);
     {
     StageTimer tm(h, st, SRQ_STAGE_RESIDUAL);
     // whatever the quantize stage has not already produced
@@ -908,6 +935,24 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     } else if (path_a == 3) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.A_int, Kc, p.RB_int, Kc, e1, st));
+    } else if (path_a == kPathColblock) {
+      // dense strip of the k kept almost everywhere on the matrix cores (one K-tile), then the
+      // remainder of the CSR on the vector ALUs; with debug outputs the second adds its raw sums
+      // to the first's
+      {
+        StageTimer tm(h, st, SRQ_STAGE_TERM1_PREP);
+        SRQ_HIP(h, launch_strip_gather(p.A_int, Kc, p.mask_a, K, M, p.klist_a, p.strip_a, st));
+        SRQ_HIP(h, launch_strip_gather(p.RB_int, Kc, nullptr, K, N, p.klist_a, p.strip_rb, st));
+      }
+      StageTimer tm(h, st, SRQ_STAGE_TERM1);
+      GemmEpilogue es = e1;
+      es.final_scale = 0;
+      if (!dbg) es.run_if_nonzero = p.nstrip;
+      SRQ_HIP(h, launch_gemm_i8(M, N, kStripK, p.strip_a, kStripK, p.strip_rb, kStripK, es, st));
+      GemmEpilogue ev = e1;
+      ev.dint_add = dbg ? 1 : 0;
+      SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.a_ptr, nullptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, ev, st,
+                                  p.kflag_a));
     } else if (path_a == kPath24) {
       // 2:4 part on the sparse matrix cores, then the spilled entries on the vector ALUs
       {
@@ -937,6 +982,21 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     } else if (path_b == 3) {
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
       SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.RA_int, Kc, p.B_int, Kc, e2, st));
+    } else if (path_b == kPathColblock) {
+      {
+        StageTimer tm(h, st, SRQ_STAGE_TERM2_PREP);
+        SRQ_HIP(h, launch_strip_gather(p.B_int, Kc, p.mask_b, K, N, p.klist_b, p.strip_b, st));
+        SRQ_HIP(h, launch_strip_gather(p.RA_int, Kc, nullptr, K, M, p.klist_b, p.strip_ra, st));
+      }
+      StageTimer tm(h, st, SRQ_STAGE_TERM2);
+      GemmEpilogue es = e2;
+      es.final_scale = 0;
+      if (!dbg) es.run_if_nonzero = p.nstrip + 1;
+      SRQ_HIP(h, launch_gemm_i8(M, N, kStripK, p.strip_ra, kStripK, p.strip_b, kStripK, es, st));
+      GemmEpilogue ev = e2;
+      ev.dint_add = dbg ? 1 : 0;
+      SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.b_ptr, nullptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, ev, st,
+                                  p.kflag_b));
     } else if (path_b == kPath24) {
       {
         StageTimer tm(h, st, SRQ_STAGE_TERM2_PREP);

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(64) void spmm_valu_kernel(int64_t nvec, int64_t nel
                                                        const int32_t* __restrict__ idx,
                                                        const int8_t* __restrict__ val, int64_t capacity,
                                                        const int8_t* __restrict__ R, int64_t ldr,
-                                                       GemmEpilogue ep) {
+                                                       GemmEpilogue ep, const uint32_t* __restrict__ kflag) {
   if (guard_tripped(ep)) return;
   const int64_t v = blockIdx.y;
   const int64_t e0 = (int64_t)blockIdx.x * kBlockElems + threadIdx.x * kLaneElems;
@@ -33,7 +33,9 @@ __global__ __launch_bounds__(64) void spmm_valu_kernel(int64_t nvec, int64_t nel
   if (e0 < nelem) {
     for (int64_t p = p0; p < p1; ++p) {
       const int a = val[p];
-      const int8_t* src = R + (int64_t)idx[p] * ldr + e0;
+      const int32_t k = idx[p];
+      if (kflag && ((kflag[k >> 5] >> (k & 31)) & 1u)) continue;   // this k belongs to the dense strip
+      const int8_t* src = R + (int64_t)k * ldr + e0;
       if (vec) {
         int w = *reinterpret_cast<const int*>(src);
         acc[0] += a * (int)(int8_t)(w & 0xff);
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(64) void spmm_valu_kernel(int64_t nvec, int64_t nel
       int64_t i = SIDE == 0 ? v : e;
       int64_t j = SIDE == 0 ? e : v;
       float d = (float)acc[t] * (ep.s_row[i] * ep.s_col[j]);
-      if (ep.D_int) ep.D_int[i * ep.ldd + j] = acc[t];
+      if (ep.D_int) ep.D_int[i * ep.ldd + j] = acc[t] + (ep.dint_add ? ep.D_int[i * ep.ldd + j] : 0);
       float out = ep.C[i * ep.ldc + j] + d;
       if (ep.final_scale) {
         out = ep.alpha * out;
@@ -109,14 +111,17 @@ __device__ __forceinline__ int word_of(word1_t x, int) { return x; }
 __device__ __forceinline__ int word_of(word2_t x, int i) { return i == 0 ? x.x : x.y; }
 __device__ __forceinline__ int word_of(word4_t x, int i) { return i == 0 ? x.x : i == 1 ? x.y : i == 2 ? x.z : x.w; }
 
-template <int SIDE, int LE>
+// FILTER: entries whose index is flagged in `kflag` (a bitmap over k) are skipped; the 64 pairs a
+// wave fetches at a time are then walked through the ballot of the kept ones instead of lane by lane.
+template <int SIDE, int LE, bool FILTER>
 __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t nelem,
                                                         const int32_t* __restrict__ ptr,
                                                         const int32_t* __restrict__ ptr_end,
                                                         const int32_t* __restrict__ idx,
                                                         const int8_t* __restrict__ val, int64_t capacity,
                                                         const int8_t* __restrict__ R, int64_t ldr,
-                                                        GemmEpilogue ep, int nvb, int nch, bool cvec) {
+                                                        GemmEpilogue ep, int nvb, int nch, bool cvec,
+                                                        const uint32_t* __restrict__ kflag) {
   constexpr int E = 64 * LE;
   constexpr int LDT = E + 1;                       // LDS row stride in words (side 1)
   extern __shared__ int tile[];
@@ -156,20 +161,44 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
         const int cnt = p1 - pb < 64 ? p1 - pb : 64;
         uint32_t ro = 0;                             // padding pairs: value 0 times row 0
         int aa = 0;
-        if (lane < cnt) { ro = (uint32_t)idx[pb + lane] * (uint32_t)ldr; aa = val[pb + lane]; }
-        const int ng = (cnt + kPairUnroll - 1) / kPairUnroll;
+        bool kept = false;
+        if (lane < cnt) {
+          const uint32_t k = (uint32_t)idx[pb + lane];
+          ro = k * (uint32_t)ldr;
+          aa = val[pb + lane];
+          kept = !FILTER || !((kflag[k >> 5] >> (k & 31)) & 1u);
+        }
+        // FILTER: the lanes holding pairs that are not part of the dense strip, walked in order by
+        // two cursors (one for the gathers being issued, one for those being consumed)
+        unsigned long long m_issue = FILTER ? __ballot(kept) : 0ull, m_use = m_issue;
+        const int npairs = FILTER ? __popcll(m_issue) : cnt;
+        const int ng = (npairs + kPairUnroll - 1) / kPairUnroll;
         words_t xa[kPairUnroll], xb[kPairUnroll];
         auto issue = [&](words_t (&x)[kPairUnroll], int g) {
 #pragma unroll
           for (int u = 0; u < kPairUnroll; ++u) {
-            const uint32_t r = __builtin_amdgcn_readlane(ro, g * kPairUnroll + u);   // row offset in bytes, < 2^32
+            uint32_t r;
+            if (FILTER) {
+              const int l = m_issue ? __builtin_ctzll(m_issue) : 0;
+              r = m_issue ? __builtin_amdgcn_readlane(ro, l) : 0u;
+              m_issue &= m_issue - 1ull;
+            } else {
+              r = __builtin_amdgcn_readlane(ro, g * kPairUnroll + u);   // row offset in bytes, < 2^32
+            }
             gather(x[u], rsrc, r, eoff);
           }
         };
         auto consume = [&](words_t (&x)[kPairUnroll], int g) {
 #pragma unroll
           for (int u = 0; u < kPairUnroll; ++u) {
-            const int a = __builtin_amdgcn_readlane(aa, g * kPairUnroll + u) & 0xff;
+            int a;
+            if (FILTER) {
+              const int l = m_use ? __builtin_ctzll(m_use) : 0;
+              a = m_use ? (__builtin_amdgcn_readlane(aa, l) & 0xff) : 0;
+              m_use &= m_use - 1ull;
+            } else {
+              a = __builtin_amdgcn_readlane(aa, g * kPairUnroll + u) & 0xff;
+            }
 #pragma unroll
             for (int t = 0; t < LE; ++t)
               acc[t] = __builtin_amdgcn_sdot4(word_of(x[u], t >> 2), a << (8 * (t & 3)), acc[t], false);
@@ -220,7 +249,7 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
 #pragma unroll
         for (int t = 0; t < LE; ++t) {
           const float d = (float)acc[t] * (sr * ep.s_col[e0 + t]);
-          if (ep.D_int) ep.D_int[v * ep.ldd + e0 + t] = acc[t];
+          if (ep.D_int) ep.D_int[v * ep.ldd + e0 + t] = acc[t] + (ep.dint_add ? ep.D_int[v * ep.ldd + e0 + t] : 0);
           float out = c[t] + d;
           if (ep.final_scale) {
             out = ep.alpha * out;
@@ -272,7 +301,7 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
       if (i >= nelem || jj >= nvec) continue;
       const int a = tile[j * LDT + e];
       const float d = (float)a * (ep.s_row[i] * sc);
-      if (ep.D_int) ep.D_int[i * ep.ldd + jj] = a;
+      if (ep.D_int) ep.D_int[i * ep.ldd + jj] = a + (ep.dint_add ? ep.D_int[i * ep.ldd + jj] : 0);
       float out = ep.C[i * ep.ldc + jj] + d;
       if (ep.final_scale) {
         out = ep.alpha * out;
@@ -286,7 +315,7 @@ __global__ __launch_bounds__(256) void spmm_tile_kernel(int64_t nvec, int64_t ne
 template <int SIDE, int LE>
 hipError_t launch_tile(int64_t nvec, int64_t nelem, const int32_t* ptr, const int32_t* ptr_end, const int32_t* idx,
                        const int8_t* val, int64_t capacity, const int8_t* R, int64_t ldr,
-                       const GemmEpilogue& ep, hipStream_t st) {
+                       const GemmEpilogue& ep, const uint32_t* kflag, hipStream_t st) {
   constexpr int E = 64 * LE;
   const int64_t nvb = (nvec + kVecPerBlock - 1) / kVecPerBlock;
   const int64_t nch = (nelem + E - 1) / E;
@@ -296,8 +325,12 @@ hipError_t launch_tile(int64_t nvec, int64_t nelem, const int32_t* ptr, const in
                     (reinterpret_cast<uintptr_t>(ep.s_col) & 15) == 0 &&
                     (!ep.Cin || ((reinterpret_cast<uintptr_t>(ep.Cin) & 15) == 0 && ep.ldcin % 4 == 0));
   const size_t lds = SIDE == 1 ? (size_t)kVecPerBlock * (E + 1) * sizeof(int) : 0;
-  hipLaunchKernelGGL((spmm_tile_kernel<SIDE, LE>), dim3((unsigned)blocks), dim3(256), lds, st, nvec, nelem,
-                     ptr, ptr_end, idx, val, capacity, R, ldr, ep, (int)nvb, (int)nch, cvec);
+  if (kflag)
+    hipLaunchKernelGGL((spmm_tile_kernel<SIDE, LE, true>), dim3((unsigned)blocks), dim3(256), lds, st, nvec, nelem,
+                       ptr, ptr_end, idx, val, capacity, R, ldr, ep, (int)nvb, (int)nch, cvec, kflag);
+  else
+    hipLaunchKernelGGL((spmm_tile_kernel<SIDE, LE, false>), dim3((unsigned)blocks), dim3(256), lds, st, nvec, nelem,
+                       ptr, ptr_end, idx, val, capacity, R, ldr, ep, (int)nvb, (int)nch, cvec, kflag);
   return hipGetLastError();
 }
 
@@ -313,13 +346,14 @@ bool tile_ok(int64_t nvec, int64_t nelem, int64_t K, const int8_t* R, int64_t ld
 
 hipError_t launch_spmm_valu(int side, int64_t nvec, int64_t nelem, int64_t K, const int32_t* ptr,
                             const int32_t* ptr_end, const int32_t* idx, const int8_t* val, int64_t capacity,
-                            const int8_t* R, int64_t ldr, const GemmEpilogue& ep, hipStream_t st) {
+                            const int8_t* R, int64_t ldr, const GemmEpilogue& ep, hipStream_t st,
+                            const uint32_t* kflag) {
   if (nvec <= 0 || nelem <= 0) return hipSuccess;
   if (!ptr_end) ptr_end = ptr + 1;                 // plain CSR / CSC
   if (side == 0 && tile_ok(nvec, nelem, K, R, ldr, 8))
-    return launch_tile<0, 8>(nvec, nelem, ptr, ptr_end, idx, val, capacity, R, ldr, ep, st);
+    return launch_tile<0, 8>(nvec, nelem, ptr, ptr_end, idx, val, capacity, R, ldr, ep, kflag, st);
   if (side == 1 && tile_ok(nvec, nelem, K, R, ldr, 4))
-    return launch_tile<1, 4>(nvec, nelem, ptr, ptr_end, idx, val, capacity, R, ldr, ep, st);
+    return launch_tile<1, 4>(nvec, nelem, ptr, ptr_end, idx, val, capacity, R, ldr, ep, kflag, st);
   const int64_t kMaxY = 65535;
   for (int64_t v0 = 0; v0 < nvec; v0 += kMaxY) {   // gridDim.y is limited to 65535
     int64_t nv = nvec - v0 < kMaxY ? nvec - v0 : kMaxY;
@@ -341,10 +375,10 @@ hipError_t launch_spmm_valu(int side, int64_t nvec, int64_t nelem, int64_t K, co
     dim3 grid((unsigned)((nelem + kBlockElems - 1) / kBlockElems), (unsigned)nv);
     if (side == 0)
       hipLaunchKernelGGL(spmm_valu_kernel<0>, grid, dim3(64), 0, st, nv, nelem, p2, q2, idx, val, capacity, R,
-                         ldr, e2);
+                         ldr, e2, kflag);
     else
       hipLaunchKernelGGL(spmm_valu_kernel<1>, grid, dim3(64), 0, st, nv, nelem, p2, q2, idx, val, capacity, R,
-                         ldr, e2);
+                         ldr, e2, kflag);
   }
   return hipGetLastError();
 }

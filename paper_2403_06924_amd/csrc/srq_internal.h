@@ -53,10 +53,15 @@ struct GemmEpilogue {
   // so that C stays the uncorrected first product instead of receiving a truncated correction.
   const int64_t* guard_nnz;   // device int64[2]: kept entries of A' and B' (null: no guard)
   int64_t guard_cap_a, guard_cap_b;
+  // a product that only matters when a device-side count is non-zero (the dense strip of the
+  // column-block execution): when set and *run_if_nonzero == 0 the kernel does nothing
+  const int32_t* run_if_nonzero;
+  int dint_add;               // vector-ALU kernels: add the raw sums to D_int instead of storing them
 };
 
 // true when the epilogue's overflow guard is set and tripped (wave-uniform: scalar loads)
 static __device__ __forceinline__ bool guard_tripped(const GemmEpilogue& ep) {
+  if (ep.run_if_nonzero && *ep.run_if_nonzero == 0) return true;
   return ep.guard_nnz && (ep.guard_nnz[0] > ep.guard_cap_a || ep.guard_nnz[1] > ep.guard_cap_b);
 }
 
@@ -205,7 +210,20 @@ hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* 
 // Vector v owns the pairs [ptr[v], ptr_end[v]); ptr_end == null means plain CSR (ptr + 1).
 hipError_t launch_spmm_valu(int side, int64_t nvec, int64_t nelem, int64_t K, const int32_t* ptr,
                             const int32_t* ptr_end, const int32_t* idx, const int8_t* val, int64_t capacity,
-                            const int8_t* R, int64_t ldr, const GemmEpilogue& ep, hipStream_t st);
+                            const int8_t* R, int64_t ldr, const GemmEpilogue& ep, hipStream_t st,
+                            const uint32_t* kflag = nullptr);   // kflag: bitmap over k of entries to skip
+
+// ---- column-block execution (colblock.hip): the k kept in at least min_keep_ratio of the vectors
+// (at most kStripK of them) become a dense strip.  count: int32[mask_words(K) * 64] scratch;
+// klist: int32[kStripK]; kflag: uint32[mask_words(K) * 2]; nstrip: int32[1]
+constexpr int kStripK = 128;
+hipError_t launch_colblock_pick(const uint64_t* mask, int64_t nvec, int64_t K, double min_keep_ratio,
+                                int32_t* count, int32_t* klist, uint32_t* kflag, int32_t* nstrip,
+                                hipStream_t st);
+// strip[v][c] = Q[v][klist[c]] (only where the keep-bit is set, if a mask is given), zero-padded
+// to kStripK columns
+hipError_t launch_strip_gather(const int8_t* Q, int64_t ldq, const uint64_t* mask, int64_t K, int64_t nvec,
+                               const int32_t* klist, int8_t* strip, hipStream_t st);
 
 // ---- 2:4-structured execution (sparse24.hip, gemm_sparse24.hip)
 // split of a zero-filled expansion into 2:4 codes + position nibbles + a spill list

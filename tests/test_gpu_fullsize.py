@@ -187,6 +187,13 @@ def test_c4_rectangular_sampled(srq, b):
     sampled_check(srq, b, "C4", 0.02, 128, seed=12)
 
 
+def test_c4_column_block_sampled(srq, b):
+    """C4 with the column-block split (the 16 outlier columns of A form the dense strip of term 1;
+    B has no such structure, its strip stays empty and is skipped on the device)."""
+    st = sampled_check(srq, b, "C4", 0.02, 128, seed=12, strategy=b.STRATEGY_COLBLOCK, bit_identical=False)
+    assert st["path_a"] == 5 and st["path_b"] == 5
+
+
 @pytest.mark.parametrize("density", [0.05, 0.20, 0.50])
 def test_c5_wide_range_sampled(srq, b, density):
     sampled_check(srq, b, "C5", density, 48, seed=13)

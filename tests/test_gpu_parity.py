@@ -270,7 +270,7 @@ def check_against_oracle(srq, b, A, B, theta_a, theta_b, *, bits=8, rnd=0, strat
             if st["path_a"] != 3:                                # the dense branch counts, it does not compact
                 assert (host(im["a_idx"]) == ref.csr_a.idx).all()
                 assert (host(im["a_val"]) == ref.csr_a.val).all()
-            assert st["path_a"] == (3 if ref.dense_a else st["path_a"]) and st["path_a"] in (1, 2, 3)
+            assert st["path_a"] == (3 if ref.dense_a else st["path_a"]) and st["path_a"] in (1, 2, 3, 5)
             assert (host(dbg["DR1_int"]) == ref.DR1_int).all()
         if not np.isinf(theta_b):
             assert st["nnz_b"] == ref.csc_b.nnz
@@ -381,6 +381,48 @@ def test_structured_2to4_execution(srq, b, shape, density):
                                      C_in=dev(Cin))
     refab = o.compensated_gemm(A, B, ta, tb, thresh_a=t_a, thresh_b=t_b, alpha=0.5, beta=-1.5, C_in=Cin)
     assert rel_fro(refab.C, host(Cab)) <= REL_TOL
+
+
+@pytest.mark.parametrize("shape", [(256, 384, 512), (192, 200, 300), (512, 1024, 4096), (130, 257, 129)])
+def test_column_block_execution(srq, b, shape):
+    """SRQ_STRATEGY_COLBLOCK on an operand with whole outlier columns (the C4 recipe: 16 columns of
+    A times 50) and, on the other side, an operand whose first rows are large (whole k-columns of
+    the transposed B): the indices kept in at least 90 % of the vectors run as a dense strip on the
+    matrix cores, the rest of the CSR on the vector ALUs.  Every stage against the oracle with the
+    raw INT32 sums of the two parts added up (bit-exact), then the timed configuration without
+    debug outputs against the oracle and against the plain vector-ALU execution."""
+    M, N, K = shape
+    A, B = wl.make_inputs("C4", M, N, K)
+    B = B.copy()
+    B[:5, :] *= np.float32(40.0)                                 # five k kept in (nearly) every column of B
+    plain = o.quantized_product(A, B)
+    drow, dcol = o.abs_means(plain.D_F)
+    da = min(0.9, 16.0 / K + 0.02)
+    ta = wl.theta_for_density(A, drow, "row", da)
+    tb = wl.theta_for_density(B, dcol, "col", 5.0 / K + 0.02)
+    ref, C, st = check_against_oracle(srq, b, A, B, ta, tb, strategy=b.STRATEGY_COLBLOCK)
+    assert st["path_a"] == 5 and st["path_b"] == (5 if N % 4 == 0 else 1)   # (unaligned B: no keep-mask, plain CSR)
+    # the structure is there: some k are kept in at least 90 % of the vectors of either operand
+    mask_a = o.select_mask(A, host(srq.intermediates(M, N, K)["t_a"]), "row")
+    mask_b = o.select_mask(B, host(srq.intermediates(M, N, K)["t_b"]), "col")
+    assert (mask_a.mean(axis=0) >= 0.9).sum() >= 1 and (mask_b.mean(axis=1) >= 0.9).sum() >= 1
+    Cin = np.random.default_rng(6).standard_normal((M, N)).astype(np.float32)
+    for alpha, beta, cin in ((1.0, 0.0, None), (0.5, -1.5, Cin)):
+        Ct, _, _ = srq.compensated_gemm(dev(A), dev(B), ta, tb, strategy=b.STRATEGY_COLBLOCK, alpha=alpha, beta=beta,
+                                        C_in=None if cin is None else dev(cin))
+        Cv, _, _ = srq.compensated_gemm(dev(A), dev(B), ta, tb, strategy=b.STRATEGY_CSR_VALU, alpha=alpha, beta=beta,
+                                        C_in=None if cin is None else dev(cin))
+        im = srq.intermediates(M, N, K)
+        refab = o.compensated_gemm(A, B, ta, tb, thresh_a=host(im["t_a"]), thresh_b=host(im["t_b"]), alpha=alpha,
+                                   beta=beta, C_in=cin)
+        assert rel_fro(refab.C, host(Ct)) <= REL_TOL
+        assert rel_fro(host(Cv), host(Ct)) <= 1e-6
+    # an operand without such structure: the strip is empty and its product is skipped on the device
+    A2, B2 = wl.make_inputs("C2", M, N, K)
+    check_against_oracle(srq, b, A2, B2, 0.9, 0.9, strategy=b.STRATEGY_COLBLOCK)
+    C2, _, _ = srq.compensated_gemm(dev(A2), dev(B2), 0.9, 0.9, strategy=b.STRATEGY_COLBLOCK)
+    Cv2, _, _ = srq.compensated_gemm(dev(A2), dev(B2), 0.9, 0.9, strategy=b.STRATEGY_CSR_VALU)
+    assert torch.equal(C2, Cv2)
 
 
 def test_bounds_theta_inf_and_zero(srq, b):
