@@ -64,11 +64,10 @@ typedef enum srq_strategy_t {
   SRQ_STRATEGY_AUTO = 0,        /* pick per term from the measured density (synchronises)   */
   SRQ_STRATEGY_CSR_VALU = 1,    /* row-wise CSR x dense on the vector ALUs                   */
   SRQ_STRATEGY_CSR_MFMA = 2,    /* CSR expanded to zero-filled INT8 tiles, matrix cores      */
-  SRQ_STRATEGY_CSR_SMFMAC = 3,  /* expansion split into a 2:4 operand for the sparse matrix-   */
-                                /* core instruction + a spill list on the vector ALUs (needs */
-                                /* M, N multiples of 256; otherwise runs as CSR_MFMA).  The   */
-                                /* spilled part of a term is added to C separately, so C is  */
-                                /* within rounding of, not bit-identical to, the other paths  */
+  SRQ_STRATEGY_CSR_SMFMAC = 3,  /* the reduced operand in 2:4 form (two operands: the first two */
+                                /* and the third and fourth kept code of every four k), on    */
+                                /* the sparse matrix-core instruction; needs M, N multiples   */
+                                /* of 256 and K <= 32768, otherwise runs as CSR_MFMA          */
   SRQ_STRATEGY_COLBLOCK = 4     /* column-block split: the indices k kept in at least 90 % of */
                                 /* an operand's vectors (up to 128 of them: whole outlier     */
                                 /* columns) form a dense strip that runs on the matrix cores; */
@@ -248,7 +247,7 @@ size_t srq_static_scratch_bytes(void);
  *   side = SRQ_AXIS_COL: DR = RA.B', (ptr,idx,val) = CSC of B' (N vectors over K), Rq = RA codes.
  * Rq layout: CSR_VALU wants the residual codes k-major (RB element-major K x N, ld >= N;
  * RA element-major K x M, ld >= M); CSR_MFMA wants them K-contiguous (RB vector-major
- * N x K; RA vector-major M x K; ld >= K).  SRQ_STRATEGY_AUTO and SRQ_STRATEGY_CSR_SMFMAC
+ * N x K; RA vector-major M x K; ld >= K).  SRQ_STRATEGY_AUTO, SRQ_STRATEGY_CSR_SMFMAC and SRQ_STRATEGY_COLBLOCK
  * (which needs both layouts) are not accepted here.
  * s_row[M] / s_col[N] are the scales paired with rows / columns of C for this term.
  * DR_int (ld = ldc) may be NULL. */

@@ -61,9 +61,9 @@ inline int strategy_path(srq_strategy_t s) {
        : s == SRQ_STRATEGY_COLBLOCK ? kPathColblock : kPathMfma;
 }
 // which layouts of the OTHER operand's residual codes an execution reads: k-major for the vector
-// ALUs (also the spill of the 2:4 split and the remainder of the column-block split),
+// ALUs (also the remainder of the column-block split),
 // K-contiguous for the matrix cores
-inline bool path_reads_em(int path) { return path == kPathValu || path == kPath24 || path == kPathColblock; }
+inline bool path_reads_em(int path) { return path == kPathValu || path == kPathColblock; }
 inline bool path_reads_vm(int path) { return path >= kPathMfma; }
 
 // share of an operand's vectors that must keep an index k for k to join the dense strip
@@ -99,13 +99,10 @@ struct Plan {
   int32_t *a_idx, *b_idx;
   int8_t *a_val, *b_val;
   int64_t cap_a, cap_b;
-  // 2:4 form of the reduced operands: kept codes, position nibbles, spill lists
-  int8_t *a24v, *b24v;
-  uint8_t *a24n, *b24n;
-  int32_t *sa_begin, *sa_end, *sb_begin, *sb_end, *sa_idx, *sb_idx;
-  int8_t *sa_val, *sb_val;
-  unsigned long long* sp_total;   // [2]
-  int64_t cap_sa, cap_sb;
+  // 2:4 form of the reduced operands: codes and position nibbles of P1 and P2, overflow flags
+  int8_t *a24v1, *a24v2, *b24v1, *b24v2;
+  uint8_t *a24n1, *a24n2, *b24n1, *b24n2;
+  uint32_t *a24f, *b24f;
   // column-block split: per-k counts, the strip's k list and flag bitmap, strips of both operands
   int32_t *kcnt, *klist_a, *klist_b, *nstrip;   // kcnt is shared by the two operands (used one after the other)
   uint32_t *kflag_a, *kflag_b;
@@ -115,8 +112,8 @@ struct Plan {
 
 int64_t tiles(int64_t n, int t) { return (n + t - 1) / t; }
 
-// workspace per kept entry: index + value, and half an entry of spill list (2:4 split)
-constexpr double kBytesPerEntry = 7.5;
+// workspace per kept entry: index + value
+constexpr double kBytesPerEntry = 5.0;
 
 // Leading dimension of the K-contiguous code matrices in the workspace: K rounded up to a
 // multiple of 128 with zeros in the padding, so that every row is 128-byte aligned and the
@@ -152,11 +149,12 @@ size_t plan_fixed(char* base, int64_t M, int64_t N, int64_t K, Plan* p) {
   p->mask_a = c.take<uint64_t>((size_t)M * mask_words(K));
   p->mask_b = c.take<uint64_t>((size_t)N * mask_words(K));
   const size_t mk256 = (size_t)((M + 255) / 256 * 256) * Kc, nk256 = (size_t)((N + 255) / 256 * 256) * Kc;
-  p->a24v = c.take<int8_t>(mk256 / 2); p->a24n = c.take<uint8_t>(mk256 / 8);
-  p->b24v = c.take<int8_t>(nk256 / 2); p->b24n = c.take<uint8_t>(nk256 / 8);
-  p->sa_begin = c.take<int32_t>(M); p->sa_end = c.take<int32_t>(M);
-  p->sb_begin = c.take<int32_t>(N); p->sb_end = c.take<int32_t>(N);
-  p->sp_total = c.take<unsigned long long>(2);
+  p->a24v1 = c.take<int8_t>(mk256 / 2); p->a24n1 = c.take<uint8_t>(mk256 / 8);
+  p->a24v2 = c.take<int8_t>(mk256 / 2); p->a24n2 = c.take<uint8_t>(mk256 / 8);
+  p->b24v1 = c.take<int8_t>(nk256 / 2); p->b24n1 = c.take<uint8_t>(nk256 / 8);
+  p->b24v2 = c.take<int8_t>(nk256 / 2); p->b24n2 = c.take<uint8_t>(nk256 / 8);
+  p->a24f = c.take<uint32_t>((size_t)sparse24_flag_words(M, Kc));
+  p->b24f = c.take<uint32_t>((size_t)sparse24_flag_words(N, Kc));
   p->kcnt = c.take<int32_t>((size_t)mask_words(K) * 64);
   p->klist_a = c.take<int32_t>(kStripK); p->klist_b = c.take<int32_t>(kStripK);
   p->nstrip = c.take<int32_t>(2);
@@ -169,10 +167,9 @@ size_t plan_fixed(char* base, int64_t M, int64_t N, int64_t K, Plan* p) {
 
 // Splits what is left of the workspace into the two compressed operands.
 bool plan_compressed(char* base, size_t bytes, int64_t M, int64_t N, int64_t K, Plan* p) {
-  if (bytes < p->fixed_bytes + 8 * kAlign) { p->cap_a = p->cap_b = p->cap_sa = p->cap_sb = 0; return false; }
+  if (bytes < p->fixed_bytes + 8 * kAlign) { p->cap_a = p->cap_b = 0; return false; }
   size_t rest = bytes - p->fixed_bytes - 8 * kAlign;
-  // 5 bytes per kept entry, and room for half as many spilled entries of the 2:4 split (at most
-  // two of the four entries of a group spill)
+  // 5 bytes per kept entry
   double total = (double)rest / kBytesPerEntry;
   double fa = (M + N) > 0 ? (double)M / (double)(M + N) : 0.5;
   int64_t cap_a = (int64_t)(total * fa), cap_b = (int64_t)(total * (1.0 - fa));
@@ -184,18 +181,12 @@ bool plan_compressed(char* base, size_t bytes, int64_t M, int64_t N, int64_t K, 
   if (cap_b > lim) cap_b = lim;
   p->cap_a = cap_a;
   p->cap_b = cap_b;
-  p->cap_sa = (cap_a + 1) / 2;
-  p->cap_sb = (cap_b + 1) / 2;
   if (base) {
     Carver c{base, p->fixed_bytes};
     p->a_idx = c.take<int32_t>(cap_a);
     p->a_val = c.take<int8_t>(cap_a);
     p->b_idx = c.take<int32_t>(cap_b);
     p->b_val = c.take<int8_t>(cap_b);
-    p->sa_idx = c.take<int32_t>(p->cap_sa);
-    p->sa_val = c.take<int8_t>(p->cap_sa);
-    p->sb_idx = c.take<int32_t>(p->cap_sb);
-    p->sb_val = c.take<int8_t>(p->cap_sb);
   }
   return true;
 }
@@ -752,6 +743,10 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   if (comp) {
     // line 9 and the branch of line 11 need the counts on the host in these modes
     const bool sync_mode = strategy == SRQ_STRATEGY_AUTO || dense_fallback_density <= 1.f;
+    // the reduced operands in 2:4 form with the dense residual codes they are multiplied with
+    // (term 2 is formed transposed: its sparse vectors are columns of C)
+    const Sparse24Operand op24a = {p.a24v1, p.a24v2, p.a24n1, p.a24n2, p.a24f, p.RB_int, Kc, p.s_a, p.s_rb};
+    const Sparse24Operand op24b = {p.b24v1, p.b24v2, p.b24n1, p.b24n2, p.b24f, p.RA_int, Kc, p.s_ra, p.s_b};
     {
     StageTimer tm(h, st, SRQ_STAGE_SELECT);
     // line 7: GetAvgVec, and the thresholds of Eq. avgQuan
@@ -828,14 +823,16 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     }
     // the 2:4 kernel needs whole 256 x 256 tiles of C and cannot write the raw sums the debug
     // block asks for: such a term takes the plain matrix-core path
-    if (path_a == kPath24 &&
-        (dbg || !gemm_sparse24_ok(M, N, Kc, p.a24v, p.a24n, p.RB_int, Kc, false, ep)))
+    // (B's 2:4 form is written from the keep-mask, which its generic, unaligned selection does not produce)
+    if (path_a == kPath24 && (dbg || !scatter24_ok(M, Kc, p.A_int, Kc) || !gemm_sparse24_ok(M, N, Kc, op24a, false, ep)))
       path_a = kPathMfma;
     if (path_b == kPath24 &&
-        (dbg || !gemm_sparse24_ok(N, M, Kc, p.b24v, p.b24n, p.RA_int, Kc, true, ep)))
+        (dbg || !fastB || !scatter24_ok(N, Kc, p.B_int, Kc) || !gemm_sparse24_ok(M, N, Kc, op24b, true, ep)))
       path_b = kPathMfma;
+    // overflow flags of the 2:4 forms start at zero (one launch clears both)
     if (path_a == kPath24 || path_b == kPath24)
-      SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.sp_total), 4, 0, st));   // spill counters
+      SRQ_HIP(h, launch_fill3_u32(path_a == kPath24 ? p.a24f : nullptr, sparse24_flag_words(M, Kc),
+                                  path_b == kPath24 ? p.b24f : nullptr, sparse24_flag_words(N, Kc), nullptr, 0, st));
     // the column-block split reads the keep-mask, which B's generic (unaligned) selection does not
     // produce: such a term runs as plain CSR on the vector ALUs
     if (path_b == kPathColblock && !fastB) path_b = kPathValu;
@@ -849,22 +846,30 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // (the dense branch multiplies the unreduced codes: its operand is counted, not compacted)
     if (term_a) {
       im.a_ptr = p.a_ptr; im.capacity_a = p.cap_a;
-      if (path_a != 3) {
+      if (path_a == kPath24) {
+        // the compaction pass writes the 2:4 form of A' (P1, P2, flags) next to the CSR arrays
+        SRQ_HIP(h, launch_scatter24(p.mask_a, M, K, Kc, p.A_int, Kc, p.a_ptr, p.a_idx, p.a_val, p.cap_a, p.a24v1,
+                                    p.a24n1, p.a24v2, p.a24n2, p.a24f, st));
+        im.a_idx = p.a_idx; im.a_val = p.a_val;
+      } else if (path_a != 3) {
         SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, Kc, p.a_ptr, p.a_idx, p.a_val, p.cap_a,
-                                       (path_a == kPathMfma || path_a == kPath24) ? p.Ad : nullptr, Kc, known_a, st));
+                                       path_a == kPathMfma ? p.Ad : nullptr, Kc, known_a, st));
         im.a_idx = p.a_idx; im.a_val = p.a_val;
       }
     }
     if (term_b && path_b == 3) {
       im.b_ptr = p.b_ptr; im.capacity_b = p.cap_b;
     } else if (term_b) {
-      if (fastB) {
+      if (path_b == kPath24) {                          // (implies fastB)
+        SRQ_HIP(h, launch_scatter24(p.mask_b, N, K, Kc, p.B_int, Kc, p.b_ptr, p.b_idx, p.b_val, p.cap_b, p.b24v1,
+                                    p.b24n1, p.b24v2, p.b24n2, p.b24f, st));
+      } else if (fastB) {
         SRQ_HIP(h, launch_scatter_mask(p.mask_b, N, K, p.B_int, Kc, p.b_ptr, p.b_idx, p.b_val, p.cap_b,
-                                       (path_b == kPathMfma || path_b == kPath24) ? p.Bd : nullptr, Kc, known_b, st));
+                                       path_b == kPathMfma ? p.Bd : nullptr, Kc, known_b, st));
       } else {
         SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
                                          p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));
-        if (path_b == kPathMfma || path_b == kPath24)
+        if (path_b == kPathMfma)
           SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, Kc, st));
       }
       im.b_ptr = p.b_ptr; im.b_idx = p.b_idx; im.b_val = p.b_val; im.capacity_b = p.cap_b;
@@ -920,12 +925,19 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     const bool pair = (path_a == kPathMfma || path_a == kPathDense) && (path_b == kPathMfma || path_b == kPathDense) &&
                       !dbg && gemm_persistent_ok(M, N, Kc, t1a, Kc, p.RB_int, Kc, e1) &&
                       gemm_persistent_ok(M, N, Kc, p.RA_int, Kc, t2b, Kc, e1);
+    // both terms in 2:4 form: one launch as well, on the sparse matrix cores
+    const bool pair24 = path_a == kPath24 && path_b == kPath24;
     if (pair) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       GemmEpilogue e12 = e1;
       e12.final_scale = scale_needed;
       const GemmSecond sec = {p.RA_int, t2b, Kc, Kc, p.s_ra, p.s_b};
       SRQ_HIP(h, launch_gemm_i8_persistent(M, N, Kc, t1a, Kc, p.RB_int, Kc, e12, st, &sec));
+    } else if (pair24) {
+      StageTimer tm(h, st, SRQ_STAGE_TERM1);
+      GemmEpilogue e12 = e1;
+      e12.final_scale = scale_needed;
+      SRQ_HIP(h, launch_gemm_i8_sparse24(M, N, Kc, op24a, false, &op24b, e12, st));
     } else if (path_a == 1) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.a_ptr, nullptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, e1, st));
@@ -954,24 +966,14 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.a_ptr, nullptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, ev, st,
                                   p.kflag_a));
     } else if (path_a == kPath24) {
-      // 2:4 part on the sparse matrix cores, then the spilled entries on the vector ALUs
-      {
-        StageTimer tm(h, st, SRQ_STAGE_TERM1_PREP);
-        SRQ_HIP(h, launch_compress24(p.Ad, Kc, M, Kc, p.a24v, p.a24n, p.sa_begin, p.sa_end,
-                                     p.sa_idx, p.sa_val, p.cap_sa, p.sp_total, st));
-      }
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
-      GemmEpilogue em = e1;
-      em.final_scale = 0;
-      SRQ_HIP(h, launch_gemm_i8_sparse24(M, N, Kc, p.a24v, p.a24n, p.RB_int, Kc, false, em, st));
-      SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.sa_begin, p.sa_end, p.sa_idx, p.sa_val, p.cap_sa, p.RB_em, N, e1,
-                                  st));
+      SRQ_HIP(h, launch_gemm_i8_sparse24(M, N, Kc, op24a, false, nullptr, e1, st));
     }
     GemmEpilogue e2 = e1;
     e2.s_row = p.s_ra; e2.s_col = p.s_b;
     e2.D_int = dbg ? dbg->DR2_int : nullptr;
     e2.final_scale = scale_needed;
-    if (pair) {
+    if (pair || pair24) {
       // (term 2 went with term 1)
     } else if (path_b == 1) {
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
@@ -998,17 +1000,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.b_ptr, nullptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, ev, st,
                                   p.kflag_b));
     } else if (path_b == kPath24) {
-      {
-        StageTimer tm(h, st, SRQ_STAGE_TERM2_PREP);
-        SRQ_HIP(h, launch_compress24(p.Bd, Kc, N, Kc, p.b24v, p.b24n, p.sb_begin, p.sb_end,
-                                     p.sb_idx, p.sb_val, p.cap_sb, p.sp_total + 1, st));
-      }
       StageTimer tm(h, st, SRQ_STAGE_TERM2);
-      GemmEpilogue em = e2;
-      em.final_scale = 0;
-      SRQ_HIP(h, launch_gemm_i8_sparse24(N, M, Kc, p.b24v, p.b24n, p.RA_int, Kc, true, em, st));
-      SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.sb_begin, p.sb_end, p.sb_idx, p.sb_val, p.cap_sb, p.RA_em, M, e2,
-                                  st));
+      SRQ_HIP(h, launch_gemm_i8_sparse24(M, N, Kc, op24b, true, nullptr, e2, st));
     }
     if (scale_needed && path_a == 0 && path_b == 0) {
       GemmEpilogue e3 = ep;

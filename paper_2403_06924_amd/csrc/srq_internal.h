@@ -226,21 +226,39 @@ hipError_t launch_strip_gather(const int8_t* Q, int64_t ldq, const uint64_t* mas
                                const int32_t* klist, int8_t* strip, hipStream_t st);
 
 // ---- 2:4-structured execution (sparse24.hip, gemm_sparse24.hip)
-// split of a zero-filled expansion into 2:4 codes + position nibbles + a spill list
-// (vals / nib: K-tile-major per block of 256 vectors, (nvec rounded up to 256) * kc / 2 resp. / 8 bytes)
-hipError_t launch_compress24(const int8_t* dense, int64_t ldd, int64_t nvec, int64_t kc, int8_t* vals,
-                             uint8_t* nib, int32_t* sp_begin, int32_t* sp_end, int32_t* sp_idx,
-                             int8_t* sp_val, int64_t sp_capacity, unsigned long long* sp_total, hipStream_t st);
-// C += dequant(sparse . dense^T) (trans: C += dequant((sparse . dense^T)^T)); Mv, Nv vectors of the
-// sparse / dense operand
-bool gemm_sparse24_ok(int64_t Mv, int64_t Nv, int64_t K, const int8_t* Av, const uint8_t* An, const int8_t* Qb,
-                      int64_t ldb, bool trans, const GemmEpilogue& ep);
-hipError_t launch_gemm_i8_sparse24(int64_t Mv, int64_t Nv, int64_t K, const int8_t* Av, const uint8_t* An,
-                                   const int8_t* Qb, int64_t ldb, bool trans, const GemmEpilogue& ep,
-                                   hipStream_t st);
+// A reduced operand in 2:4 form: P1 (first two codes of a group of four k) and P2 (third and
+// fourth), each as code bytes + position nibbles in the K-tile-major layout of sparse24.hip, and
+// one flag word per (block of 256 vectors, K-tile) telling where P2 holds anything; plus the
+// dense operand it is multiplied with, and (second product of a paired launch only) the scales
+// paired with the rows and columns of C.
+struct Sparse24Operand {
+  const int8_t *vals1, *vals2;
+  const uint8_t *nib1, *nib2;
+  const uint32_t* flags;
+  const int8_t* Qb;           // dense operand, K-contiguous
+  int64_t ldb;
+  const float *s_row, *s_col;
+};
+constexpr int kSparse24MaxKTiles = 256;      // K / 128 may not exceed this (one flag row = one wave-wide load)
+// flag words per block of 256 vectors (a multiple of 4: rows start 16-byte aligned), and of a whole
+// operand including the padding that lets the product kernel read 256 words from any row start
+__host__ __device__ inline int64_t sparse24_flag_stride(int64_t kc) { return ((kc >> 7) + 3) & ~(int64_t)3; }
+inline int64_t sparse24_flag_words(int64_t nvec, int64_t kc) {
+  return ((nvec + 255) / 256) * sparse24_flag_stride(kc) + kSparse24MaxKTiles;
+}
+// compaction pass that also writes the 2:4 form (flags must be zero on entry)
+bool scatter24_ok(int64_t nvec, int64_t kc, const int8_t* Q, int64_t ldq);
+hipError_t launch_scatter24(const uint64_t* mask, int64_t nvec, int64_t veclen, int64_t kc, const int8_t* Q,
+                            int64_t ldq, const int32_t* ptr, int32_t* idx, int8_t* val, int64_t capacity,
+                            int8_t* vals1, uint8_t* nib1, int8_t* vals2, uint8_t* nib2, uint32_t* flags,
+                            hipStream_t st);
+// C (M x N) += dequant(product).  One product (second == null): `op` with its sparse vectors along
+// the rows of C (trans false) or along its columns (trans true; scales from the epilogue either
+// way).  Two products: op = term 1 (rows), *second = term 2 (columns, with its own scales).
+bool gemm_sparse24_ok(int64_t M, int64_t N, int64_t K, const Sparse24Operand& op, bool trans, const GemmEpilogue& ep);
+hipError_t launch_gemm_i8_sparse24(int64_t M, int64_t N, int64_t K, const Sparse24Operand& op, bool trans,
+                                   const Sparse24Operand* second, const GemmEpilogue& ep, hipStream_t st);
 
-// (cap_a / cap_b: entries the compressed arrays of the operand hold; a larger count sets the
-// operand's bit in srq_stats_t::overflow)
 hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b, int64_t cap_a,
                         int64_t cap_b, srq_stats_t* out, hipStream_t st);
 hipError_t launch_scale_only(int64_t M, int64_t N, const GemmEpilogue& ep, hipStream_t st);

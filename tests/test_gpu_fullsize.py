@@ -179,7 +179,7 @@ def test_c3_structured_2to4_sampled(srq, b):
     """Full size, the launch configuration `bench.py --strategy smfmac` times: the 2:4 execution of
     both correction terms against the oracle on sampled rows and columns (codes, scales, compressed
     selection of every vector in full, as for the other strategies)."""
-    st = sampled_check(srq, b, "C3", 0.05, 192, seed=11, strategy=b.STRATEGY_CSR_SMFMAC, bit_identical=False)
+    st = sampled_check(srq, b, "C3", 0.05, 192, seed=11, strategy=b.STRATEGY_CSR_SMFMAC)
     assert st["path_a"] == 4 and st["path_b"] == 4
 
 

@@ -347,11 +347,13 @@ def test_auto_repeated_calls_reuse_the_previous_choice(srq, b):
 @pytest.mark.parametrize("shape", [(256, 256, 256), (512, 768, 384), (768, 512, 200), (256, 512, 1000), (256, 256, 9000)])
 @pytest.mark.parametrize("density", [0.05, 0.3])
 def test_structured_2to4_execution(srq, b, shape, density):
-    """SRQ_STRATEGY_CSR_SMFMAC: the reduced operand is split into a 2:4 operand for the sparse
-    matrix-core instruction and a spill list (third and fourth non-zero of a group of four k) for
-    the vector ALUs.  Selection and compressed arrays are the same as on every path (bit-exact);
-    the spilled part of a term is added to C by a second kernel, so C is compared to the
-    spec tolerance and, much tighter, to the plain matrix-core execution."""
+    """SRQ_STRATEGY_CSR_SMFMAC: the compaction pass writes the reduced operand as two operands of
+    2:4 form for the sparse matrix-core instruction (first two / third and fourth non-zero code of
+    every group of four k; the second is multiplied only where it holds anything).  Selection and
+    compressed arrays are the same as on every path (bit-exact); both parts feed the same INT32
+    accumulators, so C is bit-identical to the plain matrix-core execution (and within the
+    spec tolerance of the oracle, in practice identical).  Densities of 5 % and 30 %: the
+    second operand is nearly empty resp. needed almost everywhere."""
     M, N, K = shape
     A, B = wl.make_inputs("C2", M, N, K)
     plain = o.quantized_product(A, B)
@@ -374,13 +376,23 @@ def test_structured_2to4_execution(srq, b, shape, density):
     assert (b_ptr == ref.csc_b.ptr).all() and (b_idx == ref.csc_b.idx).all() and (b_val == ref.csc_b.val).all()
     assert rel_fro(ref.C, C24) <= REL_TOL
     C2, _, _ = srq.compensated_gemm(dev(A), dev(B), ta, tb, strategy=b.STRATEGY_CSR_MFMA)
-    assert rel_fro(host(C2), C24) <= 1e-6
-    # with alpha and beta the scaling is applied once, after the last spill pass
+    assert (host(C2) == C24).all()
+    # with alpha and beta the scaling is applied once, after the second term
     Cin = np.random.default_rng(5).standard_normal((M, N)).astype(np.float32)
     Cab, _, _ = srq.compensated_gemm(dev(A), dev(B), ta, tb, strategy=b.STRATEGY_CSR_SMFMAC, alpha=0.5, beta=-1.5,
                                      C_in=dev(Cin))
     refab = o.compensated_gemm(A, B, ta, tb, thresh_a=t_a, thresh_b=t_b, alpha=0.5, beta=-1.5, C_in=Cin)
     assert rel_fro(refab.C, host(Cab)) <= REL_TOL
+    # one term alone on the sparse matrix cores (the other operand is not reduced): the unpaired
+    # launches, rows of C resp. columns of C
+    inf = float("inf")
+    for tha, thb in ((ta, inf), (inf, tb)):
+        C1, _, _ = srq.compensated_gemm(dev(A), dev(B), tha, thb, strategy=b.STRATEGY_CSR_SMFMAC, stats=stats)
+        C1m, _, _ = srq.compensated_gemm(dev(A), dev(B), tha, thb, strategy=b.STRATEGY_CSR_MFMA)
+        torch.cuda.synchronize()
+        st1 = b.read_stats(stats)
+        assert (st1["path_a"], st1["path_b"]) == ((4, 0) if np.isinf(thb) else (0, 4))
+        assert torch.equal(C1, C1m)
 
 
 @pytest.mark.parametrize("shape", [(256, 384, 512), (192, 200, 300), (512, 1024, 4096), (130, 257, 129)])
