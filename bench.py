@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--no-accuracy", action="store_true")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the timing of the plain (theta=inf) and unreduced (theta=0) variants")
+    ap.add_argument("--stage", default=None, choices=["quantize", "build_sparse_residual"],
+                    help="time one staged entry point on the workload's operands instead of the whole path "
+                         "(prints its own JSON line: achieved GB/s against the HBM peak)")
     ap.add_argument("--report", default=None, help="also write the full report to this JSON file")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (reference point for the FETCH_SIZE / "
@@ -84,6 +87,54 @@ def cpu_baseline(name, A, B, theta_a, theta_b):
                       % (ms - 1, ms, N, K, dt)}
 
 
+def stage_bench(args, b, torch, h, w, Ad, Bd, sa, sb, drow, dcol, theta_a, theta_b):
+    """srq_quantize or srq_build_sparse_residual on both operands of the workload (A by rows, B by
+    columns), HIP-event timed on the launch stream; algorithmic bytes: quantize reads 4 B and writes
+    1 B per element; build_sparse_residual reads each element for the residual codes (4 B in, 1 B
+    out), once more for the selection (4 B) and writes 5 B per kept entry and 4 B per vector."""
+    M, N, K = w.M, w.N, w.K
+    Qa, sa, lam_a = h.quantize(Ad, b.AXIS_ROW)
+    Qb, sb, lam_b = h.quantize(Bd, b.AXIS_COL)
+    t_a = (drow * theta_a).contiguous()
+    t_b = (dcol * theta_b).contiguous()
+    nnz = [0, 0]
+
+    def run():
+        if args.stage == "quantize":
+            h.quantize(Ad, b.AXIS_ROW)
+            h.quantize(Bd, b.AXIS_COL)
+        else:
+            ra = h.build_sparse_residual(Ad, b.AXIS_ROW, sa, lam_a, t_a, capacity=int(M * K * 0.08))
+            rb = h.build_sparse_residual(Bd, b.AXIS_COL, sb, lam_b, t_b, capacity=int(N * K * 0.08))
+            nnz[0], nnz[1] = ra["nnz"], rb["nnz"]
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    elems = float(M * K + K * N)
+    if args.stage == "quantize":
+        nbytes = 5.0 * elems + 8.0 * (M + N)
+        kept = None
+    else:
+        kept = int(nnz[0].item()) + int(nnz[1].item())
+        nbytes = 9.0 * elems + 5.0 * kept + 4.0 * (M + N + 2)
+    print(json.dumps({"metric": "achieved HBM GB/s of srq_%s (A by rows + B by columns)" % args.stage,
+                      "value": nbytes / (ms * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "dtype": "int8",
+                      "data": "synthetic", "config": {"workload": "%s: M=%d N=%d K=%d" % (w.name, M, N, K)},
+                      "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                                   "unit": "GB/s", "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                   "algorithmic_bytes": nbytes, "kept_entries": kept,
+                                   "note": "includes the binding's output allocations (torch caching allocator)"}}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -122,6 +173,10 @@ def main():
     _, _, drow, dcol = h.gemm_i8(Qa, sa, Qb, sb)
     theta_a = wl.theta_for_density(Ad, drow, 0, density)
     theta_b = wl.theta_for_density(Bd, dcol, 1, density)
+    if args.stage:
+        stage_bench(args, b, torch, h, w, Ad, Bd, sa, sb, drow, dcol, theta_a, theta_b)
+        h.close()
+        return
     del Qa, Qb
     torch.cuda.empty_cache()
 

@@ -199,6 +199,11 @@ size_t stage_bytes(int64_t M, int64_t N, int64_t K) {
   b += align_up(((size_t)select_chunks(K) * big + (size_t)select_chunks(big) * K) * 4);  // counts
   b += align_up(((size_t)tiles(N, gemm_tile_n()) * M + (size_t)tiles(M, gemm_tile_m()) * N) * 8);
   b += align_up(big * K);                                               // expanded operand
+  // srq_build_sparse_residual's streaming path on an operand of up to max(M,N) x K or K x max(M,N):
+  // three vectors of per-vector values, the keep-mask and the codes (rows padded to 16)
+  const size_t fast = align_up(mx * 4) * 3 + align_up((big * ((size_t)K + 63) / 64 + (size_t)K * ((big + 63) / 64)) * 8) +
+                      align_up(big * (((size_t)K + 15) / 16 * 16) + (size_t)K * ((big + 15) / 16 * 16));
+  if (b < fast) b = fast;
   return b + 8 * kAlign;
 }
 
@@ -452,6 +457,52 @@ srq_status_t srq_build_sparse_residual(srq_handle_t h, const float* X, int64_t r
   if (s) return s;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   int qmax = qmax_of_bits(bits), trunc = round == SRQ_ROUND_TRUNC;
+  // ---- streaming kernels for aligned operands (the kernels of the whole-path call): codes of X go
+  // to the workspace, the keep-mask is built in one more read of X and compacted from there
+  if (rows > 0 && cols > 0) {
+    const int64_t ldqw = (veclen + 15) / 16 * 16;
+    Carver f{reinterpret_cast<char*>(h->ws), 0};
+    float* rlam_w = f.take<float>(nvec);
+    int32_t* tot_w = f.take<int32_t>(nvec);
+    uint32_t* ramax_w = f.take<uint32_t>(nvec);
+    uint64_t* mask_w = f.take<uint64_t>((size_t)nvec * mask_words(veclen));
+    int8_t* q_w = f.take<int8_t>((size_t)nvec * ldqw);
+    const bool fits = f.off <= h->ws_bytes;
+    const bool vm = r_layout == SRQ_LAYOUT_VECTOR_MAJOR;
+    auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+    if (fits && axis == SRQ_AXIS_ROW && (!do_res || vm) &&
+        rows_fused_ok(X, cols, ldx, q_w, ldqw, do_res ? Rq : nullptr, ldr)) {
+      SRQ_HIP(h, launch_rows_fused(X, rows, cols, ldx, qmax, trunc, q_w, ldqw, nullptr, nullptr, do_res ? Rq : nullptr,
+                                   ldr, do_res ? rscale : nullptr, do_res ? rlam_w : nullptr, st, scale, lambda));
+      if (do_sel) {
+        SRQ_HIP(h, launch_rows_mask(X, rows, cols, ldx, thresh, mask_w, tot_w, st));
+        SRQ_HIP(h, launch_scan_pair(tot_w, nvec, ptr, nnz_dev, nullptr, 0, nullptr, nullptr, st));
+        SRQ_HIP(h, launch_scatter_mask(mask_w, nvec, veclen, q_w, ldqw, ptr, idx, val, capacity, nullptr, 0, -1, st));
+      }
+      return SRQ_STATUS_OK;
+    }
+    const bool r_ok = !do_res || (al16(rscale) && (vm ? (al16(Rq) && (ldr % 16) == 0)
+                                                    : ((reinterpret_cast<uintptr_t>(Rq) & 3) == 0 && (ldr % 4) == 0)));
+    if (fits && axis == SRQ_AXIS_COL && cols_pass_ok(X, cols, ldx) && al16(scale) && al16(lambda) &&
+        (!do_sel || al16(thresh)) && r_ok) {
+      SRQ_HIP(h, launch_fill3_u32(ramax_w, nvec, reinterpret_cast<uint32_t*>(tot_w), nvec, nullptr, 0, st));
+      SRQ_HIP(h, launch_cols_codes(X, rows, cols, ldx, qmax, trunc, scale, lambda, q_w, ldqw, nullptr, 0,
+                                   do_res ? ramax_w : nullptr, st));
+      if (do_res && do_sel)
+        SRQ_HIP(h, launch_cols_mask_resid(X, rows, cols, ldx, qmax, trunc, scale, lambda, ramax_w, rscale, rlam_w,
+                                          vm ? Rq : nullptr, ldr, vm ? nullptr : Rq, ldr, thresh, mask_w, tot_w, st));
+      else if (do_res)
+        SRQ_HIP(h, launch_cols_resid_from_amax(X, rows, cols, ldx, qmax, trunc, scale, lambda, ramax_w, rscale, rlam_w,
+                                               vm ? Rq : nullptr, ldr, vm ? nullptr : Rq, ldr, st));
+      else if (do_sel)
+        SRQ_HIP(h, launch_cols_mask(X, rows, cols, ldx, thresh, mask_w, tot_w, st));
+      if (do_sel) {
+        SRQ_HIP(h, launch_scan_pair(tot_w, nvec, ptr, nnz_dev, nullptr, 0, nullptr, nullptr, st));
+        SRQ_HIP(h, launch_scatter_mask(mask_w, nvec, veclen, q_w, ldqw, ptr, idx, val, capacity, nullptr, 0, -1, st));
+      }
+      return SRQ_STATUS_OK;
+    }
+  }
   Carver c{reinterpret_cast<char*>(h->ws), 0};
   float* rlam = c.take<float>(nvec);
   int32_t* totals = c.take<int32_t>(nvec);

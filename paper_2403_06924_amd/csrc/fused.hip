@@ -59,7 +59,12 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
                                                          float* __restrict__ scale, float* __restrict__ lambda,
                                                          int8_t* __restrict__ Rq, int64_t ldr,
                                                          float* __restrict__ rscale,
-                                                         float* __restrict__ rlambda) {
+                                                         float* __restrict__ rlambda,
+                                                         // when given, the row's scale and lambda are taken
+                                                         // from here instead of from its maximum (and not
+                                                         // written back)
+                                                         const float* __restrict__ given_scale,
+                                                         const float* __restrict__ given_lambda) {
   __shared__ float sm[4];
   const int64_t row = blockIdx.x;
   const float4* src = reinterpret_cast<const float4*>(X + row * ldx);
@@ -72,9 +77,14 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
     x[i] = c4 < n4 ? load_streaming(src + c4) : make_float4(0.f, 0.f, 0.f, 0.f);
     m = fmaxf(m, fmaxf(fmaxf(fabsf(x[i].x), fabsf(x[i].y)), fmaxf(fabsf(x[i].z), fabsf(x[i].w))));
   }
-  const float amax = block_max_256(m, sm);
   float lam = 0.f, s = 0.f;
-  if (amax > 0.f) { lam = qmax / amax; s = amax / qmax; }
+  if (given_scale) {
+    lam = given_lambda[row];
+    s = given_scale[row];
+  } else {
+    const float amax = block_max_256(m, sm);
+    if (amax > 0.f) { lam = qmax / amax; s = amax / qmax; }
+  }
   unsigned* qdst = reinterpret_cast<unsigned*>(Q + row * ldq);
   float rm = 0.f;
 #pragma unroll
@@ -90,12 +100,15 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
       rm = fmaxf(rm, fmaxf(fmaxf(fabsf(x[i].x), fabsf(x[i].y)), fmaxf(fabsf(x[i].z), fabsf(x[i].w))));
     }
   }
-  if (threadIdx.x == 0) { scale[row] = s; lambda[row] = lam; }
+  if (threadIdx.x == 0 && !given_scale) { scale[row] = s; lambda[row] = lam; }
   if (!rscale) return;
   const float ramax = block_max_256(rm, sm);
   float rlam = 0.f, rs = 0.f;
   if (ramax > 0.f) { rlam = qmax / ramax; rs = ramax / qmax; }
-  if (threadIdx.x == 0) { rscale[row] = rs; rlambda[row] = rlam; }
+  if (threadIdx.x == 0) {
+    rscale[row] = rs;
+    if (rlambda) rlambda[row] = rlam;
+  }
   if (!Rq) return;                                   // residual scales only: the codes are written elsewhere
   unsigned* rdst = reinterpret_cast<unsigned*>(Rq + row * ldr);
 #pragma unroll
@@ -678,13 +691,14 @@ bool rows_fused_ok(const float* X, int64_t cols, int64_t ldx, const int8_t* Q, i
 
 hipError_t launch_rows_fused(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                              int8_t* Q, int64_t ldq, float* scale, float* lambda, int8_t* Rq, int64_t ldr,
-                             float* rscale, float* rlambda, hipStream_t st) {
+                             float* rscale, float* rlambda, hipStream_t st, const float* given_scale,
+                             const float* given_lambda) {
   if (rows <= 0) return hipSuccess;
   dim3 grid((unsigned)rows), block(256);
   const float qm = (float)qmax;
 #define SRQ_ROWS(NV4)                                                                                        \
   hipLaunchKernelGGL(rows_fused_kernel<NV4>, grid, block, 0, st, X, cols, ldx, qm, trunc, Q, ldq, scale,     \
-                     lambda, Rq, ldr, rscale, rlambda)
+                     lambda, Rq, ldr, rscale, rlambda, given_scale, given_lambda)
   if (cols <= 1024) SRQ_ROWS(1);
   else if (cols <= 2048) SRQ_ROWS(2);
   else if (cols <= 4096) SRQ_ROWS(4);

@@ -116,10 +116,13 @@ hipError_t launch_scan_totals(const int32_t* totals, int64_t nvec, int32_t* ptr,
 inline int64_t mask_words(int64_t veclen) { return (veclen + 63) / 64; }
 bool rows_fused_ok(const float* X, int64_t cols, int64_t ldx, const int8_t* Q, int64_t ldq, const int8_t* Rq,
                    int64_t ldr);
-// (rscale == null: no residual at all; Rq == null with rscale given: residual scales only)
+// (rscale == null: no residual at all; Rq == null with rscale given: residual scales only;
+//  given_scale / given_lambda: use these per-row values instead of deriving them from the row's
+//  maximum, and leave scale / lambda unwritten; rlambda may be null)
 hipError_t launch_rows_fused(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                              int8_t* Q, int64_t ldq, float* scale, float* lambda, int8_t* Rq, int64_t ldr,
-                             float* rscale, float* rlambda, hipStream_t st);
+                             float* rscale, float* rlambda, hipStream_t st, const float* given_scale = nullptr,
+                             const float* given_lambda = nullptr);
 bool rows_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* scale,
                       const float* lambda, const float* rlambda, const int8_t* Rem, int64_t ldem);
 hipError_t launch_rows_resid_em(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
