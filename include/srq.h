@@ -61,7 +61,7 @@ typedef enum srq_round_t { SRQ_ROUND_NEAREST_EVEN = 0, SRQ_ROUND_TRUNC = 1 } srq
 /* How the sparse products of Algorithm 1's SPMM line are executed.  Every strategy returns
  * the same INT32 values. */
 typedef enum srq_strategy_t {
-  SRQ_STRATEGY_AUTO = 0,        /* pick per term from the measured density (synchronises)   */
+  SRQ_STRATEGY_AUTO = 0,        /* pick per term from the measured density, on the device   */
   SRQ_STRATEGY_CSR_VALU = 1,    /* row-wise CSR x dense on the vector ALUs                   */
   SRQ_STRATEGY_CSR_MFMA = 2,    /* CSR expanded to zero-filled INT8 tiles, matrix cores      */
   SRQ_STRATEGY_CSR_SMFMAC = 3,  /* the reduced operand in 2:4 form (two operands: the first two */
@@ -150,6 +150,15 @@ srq_status_t srq_stage_workspace_bytes(int64_t M, int64_t N, int64_t K, size_t* 
  * exported s_a / lam_a / s_b / lam_b vectors hold the one matrix-wide value in every entry.
  * Host call; returns SRQ_STATUS_INVALID_ARG for an unknown mode. */
 srq_status_t srq_set_scale_mode(srq_handle_t handle, srq_scale_t mode);
+
+/* SRQ_STRATEGY_AUTO decides per term on the device, after the selection, whether the sparse
+ * product runs on the vector ALUs (1) or on the matrix cores (2).  Some intermediates are laid
+ * out for one or the other before that decision exists; the library writes them for the execution
+ * named here (0 = no expectation: the matrix cores) and, if the decision then differs, once more
+ * in the other layout.  The hint never changes a result, only the time of a call; a caller
+ * that reads srq_stats_t after a call can pass on path_a / path_b as the hint for the next call on
+ * similar operands.  Host call. */
+srq_status_t srq_set_auto_hint(srq_handle_t handle, int path_a, int path_b);
 
 /* Stage timing of srq_compensated_gemm (the per-stage time shares of Sec. 4.1.2).  When
  * enabled, the call records a pair of HIP events on `stream` around each stage;
@@ -266,16 +275,18 @@ srq_status_t srq_spmm_accumulate(srq_handle_t handle, srq_axis_t side, srq_strat
  *   dense_fallback_density   Algorithm 1's limit "s": a term whose reduced operand has
  *                      density >= s runs as a dense product on the UNREDUCED codes.  Values
  *                      > 1 switch the branch off.  Any value <= 1 makes the call synchronise
- *                      once on `stream` to read the densities, as SRQ_STRATEGY_AUTO does.
+ *                      once on `stream` to read the densities (the only synchronising mode).
  *   Cin                read only if beta != 0 (ldcin >= N); must not overlap C.
  *   stats_dev          device srq_stats_t, may be NULL.
  *   dbg                host pointer to a struct of device buffers, may be NULL.
  * An operand that is reduced (finite theta) must have fewer than 2^31 elements (INT32 row
  * pointers): SRQ_STATUS_UNSUPPORTED otherwise.
  * With dbg != NULL a CSR_SMFMAC term runs as CSR_MFMA (the 2:4 kernel has no raw-sum output).
- * With a fixed strategy (CSR_VALU, CSR_MFMA or CSR_SMFMAC) and dense_fallback_density > 1 the call only
- * enqueues kernels on `stream`: no allocation, no host read-back, no memset node, so it may be
- * recorded into a HIP graph by a capturing caller (the workspace must be attached before).
+ * With dense_fallback_density > 1 the call only enqueues kernels on `stream`, whatever the
+ * strategy (SRQ_STRATEGY_AUTO takes its decision on the device): no allocation, no host
+ * read-back, no memset node, so it may be recorded into a HIP graph by a capturing caller (the
+ * workspace must be attached before).  srq_get_intermediates then reports only what exists
+ * whatever the decision turns out to be (residual codes in the hinted layout).
  * Returns SRQ_STATUS_CAPACITY (after the first product and the selection ran: C then holds the
  * uncorrected D_F, no correction term was added) when a synchronising mode finds more kept
  * entries than the workspace was sized for.  A non-synchronising mode cannot know on the host:

@@ -27,7 +27,7 @@ EXPORTS = [
     "srq_stage_workspace_bytes", "srq_last_hip_error", "srq_status_string", "srq_quantize",
     "srq_build_sparse_residual", "srq_gemm_i8", "srq_spmm_accumulate", "srq_compensated_gemm",
     "srq_get_intermediates", "srq_profile_enable", "srq_profile_read", "srq_set_scale_mode",
-    "srq_gemm_i8_static_scratch", "srq_static_scratch_bytes",
+    "srq_gemm_i8_static_scratch", "srq_static_scratch_bytes", "srq_set_auto_hint",
 ]
 STAGES = ["quantize", "gemm", "select", "residual", "term1_prep", "term1", "term2_prep", "term2"]
 
@@ -90,6 +90,7 @@ def load():
     lib.srq_get_intermediates.argtypes = [vp, C.POINTER(Intermediates)]
     lib.srq_profile_enable.argtypes = [vp, i32]
     lib.srq_set_scale_mode.argtypes = [vp, i32]
+    lib.srq_set_auto_hint.argtypes = [vp, i32, i32]
     lib.srq_profile_read.argtypes = [vp, C.POINTER(f32)]
     for name in EXPORTS:
         if name not in ("srq_status_string", "srq_static_scratch_bytes"):
@@ -185,6 +186,11 @@ class Srq:
     def set_scale_mode(self, mode):
         """srq_set_scale_mode: SCALE_VECTOR (default) or SCALE_GLOBAL for later compensated_gemm calls."""
         self._ret(self.lib.srq_set_scale_mode(self.h, int(mode)), "srq_set_scale_mode")
+
+    def set_auto_hint(self, path_a, path_b):
+        """srq_set_auto_hint: the executions (1 vector ALUs, 2 matrix cores, 0 none) the caller expects
+        STRATEGY_AUTO to pick for term 1 / term 2 in the following calls."""
+        self._ret(self.lib.srq_set_auto_hint(self.h, int(path_a), int(path_b)), "srq_set_auto_hint")
 
     def profile_enable(self, on=True):
         self._ret(self.lib.srq_profile_enable(self.h, 1 if on else 0), "srq_profile_enable")

@@ -56,6 +56,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // and 0.75 %) were measured at 2048^3 and 4096^3.
 // execution of a correction term as reported in srq_stats_t (0: term skipped)
 constexpr int kPathValu = 1, kPathMfma = 2, kPathDense = 3, kPath24 = 4, kPathColblock = 5;
+constexpr int kPathOnDevice = 6;          // host-side marker: vector ALUs or matrix cores, decided on the device
 inline int strategy_path(srq_strategy_t s) {
   return s == SRQ_STRATEGY_CSR_VALU ? kPathValu : s == SRQ_STRATEGY_CSR_SMFMAC ? kPath24
        : s == SRQ_STRATEGY_COLBLOCK ? kPathColblock : kPathMfma;
@@ -95,6 +96,7 @@ struct Plan {
   double *row_part, *col_part;
   int32_t *cnt_a, *tot_a, *a_ptr, *cnt_b, *tot_b, *b_ptr;
   int64_t* nnz;   // [2]
+  int32_t* paths; // [2] executions SRQ_STRATEGY_AUTO decided on the device
   uint64_t *mask_a, *mask_b;   // keep-bits, one row of words per vector
   int32_t *a_idx, *b_idx;
   int8_t *a_val, *b_val;
@@ -146,6 +148,7 @@ size_t plan_fixed(char* base, int64_t M, int64_t N, int64_t K, Plan* p) {
   p->cnt_b = c.take<int32_t>((size_t)chk * N); p->tot_b = c.take<int32_t>(N);
   p->b_ptr = c.take<int32_t>(N + 1);
   p->nnz = c.take<int64_t>(2);
+  p->paths = c.take<int32_t>(2);
   p->mask_a = c.take<uint64_t>((size_t)M * mask_words(K));
   p->mask_b = c.take<uint64_t>((size_t)N * mask_words(K));
   const size_t mk256 = (size_t)((M + 255) / 256 * 256) * Kc, nk256 = (size_t)((N + 255) / 256 * 256) * Kc;
@@ -291,6 +294,13 @@ srq_status_t srq_create(srq_handle_t* handle, int device) {
 srq_status_t srq_set_scale_mode(srq_handle_t h, srq_scale_t mode) {
   if (!h || (mode != SRQ_SCALE_VECTOR && mode != SRQ_SCALE_GLOBAL)) return SRQ_STATUS_INVALID_ARG;
   h->scale_mode = (int)mode;
+  return SRQ_STATUS_OK;
+}
+
+srq_status_t srq_set_auto_hint(srq_handle_t h, int path_a, int path_b) {
+  if (!h || path_a < 0 || path_a > 2 || path_b < 0 || path_b > 2) return SRQ_STATUS_INVALID_ARG;
+  h->last_path_a = path_a;
+  h->last_path_b = path_b;
   return SRQ_STATUS_OK;
 }
 
@@ -715,6 +725,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     const bool skip_ra_vm = comp && term_b && dense_fallback_density > 1.f &&
                             (strategy == SRQ_STRATEGY_CSR_VALU ||
                              (strategy == SRQ_STRATEGY_AUTO && h->last_path_b == kPathValu));
+    // (SRQ_STRATEGY_AUTO goes by the caller's hint, srq_set_auto_hint; a wrong or missing hint only
+    // costs the pass that writes the other layout once the decision is known)
     SRQ_HIP(h, launch_rows_fused(A, M, K, lda, qmax, trunc, p.A_int, Kc, p.s_a, p.lam_a,
                                  (comp && !skip_ra_vm) ? p.RA_int : nullptr, Kc, comp ? p.s_ra : nullptr,
                                  comp ? p.lam_ra : nullptr, st));
@@ -793,7 +805,13 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   int path_a = 0, path_b = 0;
   if (comp) {
     // line 9 and the branch of line 11 need the counts on the host in these modes
-    const bool sync_mode = strategy == SRQ_STRATEGY_AUTO || dense_fallback_density <= 1.f;
+    // Only the density switch needs the counts on the host.  SRQ_STRATEGY_AUTO without it decides on
+    // the device: a small kernel turns the counts into an execution per term, and every launch
+    // that belongs to one outcome only checks that decision itself and does nothing otherwise.
+    const bool sync_mode = dense_fallback_density <= 1.f;
+    const bool auto_dev = strategy == SRQ_STRATEGY_AUTO && !sync_mode;
+    const RunIf a_on_mfma = {p.paths + 0, 1u << kPathMfma}, a_on_valu = {p.paths + 0, 1u << kPathValu};
+    const RunIf b_on_mfma = {p.paths + 1, 1u << kPathMfma}, b_on_valu = {p.paths + 1, 1u << kPathValu};
     // the reduced operands in 2:4 form with the dense residual codes they are multiplied with
     // (term 2 is formed transposed: its sparse vectors are columns of C)
     const Sparse24Operand op24a = {p.a24v1, p.a24v2, p.a24n1, p.a24n2, p.a24f, p.RB_int, Kc, p.s_a, p.s_rb};
@@ -843,7 +861,16 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
                                 (term_b && fastB) ? p.tot_b : nullptr, N, p.b_ptr, p.nnz + 1, st));
     // line 9 and the branch of line 11: which execution each term takes
     int64_t known_a = -1, known_b = -1;        // kept entries, once the host has read them
-    if (sync_mode) {
+    if (auto_dev) {
+      // (for K > 8192 the K x 512-byte slab of codes an XCD gathers from outgrows its L2 and the
+      // vector-ALU kernel loses earlier: measured crossover 0.8 % at 16384^3)
+      const double ca = K > 8192 ? kAutoMfmaDensityALongK : kAutoMfmaDensityA;
+      const double cb = K > 8192 ? kAutoMfmaDensityBLongK : kAutoMfmaDensityB;
+      SRQ_HIP(h, launch_decide_paths(p.nnz, term_a, term_b, (int64_t)ceil(ca * (double)M * (double)K),
+                                     (int64_t)ceil(cb * (double)N * (double)K), p.paths, st));
+      if (term_a) path_a = kPathOnDevice;
+      if (term_b) path_b = kPathOnDevice;
+    } else if (sync_mode) {
       h->host_nnz[0] = h->host_nnz[1] = 0;
       SRQ_HIP(h, hipMemcpyAsync(h->host_nnz, p.nnz, 2 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
       SRQ_HIP(h, hipStreamSynchronize(st));
@@ -904,7 +931,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
         im.a_idx = p.a_idx; im.a_val = p.a_val;
       } else if (path_a != 3) {
         SRQ_HIP(h, launch_scatter_mask(p.mask_a, M, K, p.A_int, Kc, p.a_ptr, p.a_idx, p.a_val, p.cap_a,
-                                       path_a == kPathMfma ? p.Ad : nullptr, Kc, known_a, st));
+                                       (path_a == kPathMfma || auto_dev) ? p.Ad : nullptr, Kc, known_a, st,
+                                       auto_dev ? a_on_mfma : kAlways));
         im.a_idx = p.a_idx; im.a_val = p.a_val;
       }
     }
@@ -916,12 +944,14 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
                                     p.b24n1, p.b24v2, p.b24n2, p.b24f, st));
       } else if (fastB) {
         SRQ_HIP(h, launch_scatter_mask(p.mask_b, N, K, p.B_int, Kc, p.b_ptr, p.b_idx, p.b_val, p.cap_b,
-                                       path_b == kPathMfma ? p.Bd : nullptr, Kc, known_b, st));
+                                       (path_b == kPathMfma || auto_dev) ? p.Bd : nullptr, Kc, known_b, st,
+                                       auto_dev ? b_on_mfma : kAlways));
       } else {
         SRQ_HIP(h, launch_select_scatter(B, K, N, ldb, SRQ_AXIS_COL, p.t_b, p.lam_b, qmax, trunc, p.b_ptr,
                                          p.cnt_b, p.b_idx, p.b_val, p.cap_b, st));
-        if (path_b == kPathMfma)
-          SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, Kc, st));
+        if (path_b == kPathMfma || auto_dev)
+          SRQ_HIP(h, launch_densify(p.b_ptr, p.b_idx, p.b_val, N, K, p.cap_b, p.Bd, Kc, st,
+                                    auto_dev ? b_on_mfma : kAlways));
       }
       im.b_ptr = p.b_ptr; im.b_idx = p.b_idx; im.b_val = p.b_val; im.capacity_b = p.cap_b;
     }
@@ -930,7 +960,30 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // (RA feeds term 2, RB feeds term 1)
     bool ra_vm = path_reads_vm(path_b), ra_em = path_reads_em(path_b);
     bool rb_vm = path_reads_vm(path_a), rb_em = path_reads_em(path_a);
-    {
+    if (auto_dev) {
+      // which layout a term reads is only known on the device: a layout the earlier stages have not
+      // written (they went by the hint) is written now, by a launch that does nothing unless the
+      // decision asks for it.  Only what is certain to exist is exported as an intermediate.
+      StageTimer tm(h, st, SRQ_STAGE_RESIDUAL);
+      auto resid_a = [&](bool vm, RunIf run) -> hipError_t {
+        if (!vm && rows_resid_em_ok(A, M, K, lda, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M))
+          return launch_rows_resid_em(A, M, K, lda, qmax, trunc, p.s_a, p.lam_a, p.lam_ra, p.RA_em, M, st, run);
+        return launch_residual_tiles(A, M, K, lda, SRQ_AXIS_ROW, p.s_a, p.lam_a, p.lam_ra, qmax, trunc,
+                                     vm ? p.RA_int : nullptr, Kc, vm ? nullptr : p.RA_em, M, st, run);
+      };
+      auto resid_b = [&](bool vm, RunIf run) -> hipError_t {
+        if (fastB)
+          return launch_cols_resid(B, K, N, ldb, qmax, trunc, p.s_b, p.lam_b, p.lam_rb, vm ? p.RB_int : nullptr, Kc,
+                                   vm ? nullptr : p.RB_em, N, st, run);
+        return launch_residual_tiles(B, K, N, ldb, SRQ_AXIS_COL, p.s_b, p.lam_b, p.lam_rb, qmax, trunc,
+                                     vm ? p.RB_int : nullptr, Kc, vm ? nullptr : p.RB_em, N, st, run);
+      };
+      if (term_b && !ra_vm_done) SRQ_HIP(h, resid_a(true, b_on_mfma));
+      if (term_b && !ra_em_done) SRQ_HIP(h, resid_a(false, b_on_valu));
+      if (term_a && !rb_vm_done) SRQ_HIP(h, resid_b(true, a_on_mfma));
+      if (term_a && !rb_em_done) SRQ_HIP(h, resid_b(false, a_on_valu));
+      ra_vm = ra_vm_done; ra_em = ra_em_done; rb_vm = rb_vm_done; rb_em = rb_em_done;
+    } else {
     StageTimer tm(h, st, SRQ_STAGE_RESIDUAL);
     // whatever the quantize stage has not already produced
     const bool need_ra_vm = ra_vm && !ra_vm_done, need_rb_vm = rb_vm && !rb_vm_done;
@@ -968,6 +1021,52 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       e1.guard_nnz = p.nnz;
       e1.guard_cap_a = (path_a && path_a != kPathDense) ? p.cap_a : kNoCap;
       e1.guard_cap_b = (path_b && path_b != kPathDense) ? p.cap_b : kNoCap;
+    }
+    if (auto_dev) {
+      // Every launch one of the four outcomes (vector ALUs / matrix cores per term) needs is
+      // enqueued; each reads the decision and returns at once unless it is its turn:
+      //   both on the matrix cores  -> the paired launch (if the shape allows it)
+      //   term t on the vector ALUs -> its sparse kernel
+      //   term t on the matrix cores, the other not (or no paired launch) -> its own dense launch
+      // The kernel of term 2 (or the pair) applies alpha / beta.
+      const uint32_t kV = 1u << kPathValu, kM = 1u << kPathMfma, kAny = ~0u;
+      GemmEpilogue e2 = e1;
+      e2.s_row = p.s_ra; e2.s_col = p.s_b;
+      e2.D_int = dbg ? dbg->DR2_int : nullptr;
+      e2.final_scale = scale_needed;
+      e1.final_scale = scale_needed && !term_b;
+      e1.paths = e2.paths = p.paths;
+      const bool pair_ok = term_a && term_b && !dbg && gemm_persistent_ok(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, e1) &&
+                           gemm_persistent_ok(M, N, Kc, p.RA_int, Kc, p.Bd, Kc, e1);
+      {
+        StageTimer tm(h, st, SRQ_STAGE_TERM1);
+        if (pair_ok) {
+          GemmEpilogue e12 = e1;
+          e12.final_scale = scale_needed;
+          e12.ok_a = kM; e12.ok_b = kM;
+          const GemmSecond sec = {p.RA_int, p.Bd, Kc, Kc, p.s_ra, p.s_b};
+          SRQ_HIP(h, launch_gemm_i8_persistent(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, e12, st, &sec));
+        }
+        if (term_a) {
+          GemmEpilogue ev = e1, em = e1;
+          ev.ok_a = kV; ev.ok_b = kAny;
+          SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.a_ptr, nullptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, ev, st));
+          em.ok_a = kM; em.ok_b = pair_ok ? ~kM : kAny;
+          SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, em, st));
+        }
+      }
+      if (term_b) {
+        StageTimer tm(h, st, SRQ_STAGE_TERM2);
+        GemmEpilogue ev = e2, em = e2;
+        ev.ok_b = kV; ev.ok_a = kAny;
+        SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.b_ptr, nullptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, ev, st));
+        em.ok_b = kM; em.ok_a = pair_ok ? ~kM : kAny;
+        SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.RA_int, Kc, p.Bd, Kc, em, st));
+      }
+      if (stats_dev)
+        SRQ_HIP(h, launch_stats(term_a ? p.nnz : nullptr, term_b ? p.nnz + 1 : nullptr, 0, 0, term_a ? p.cap_a : kNoCap,
+                                term_b ? p.cap_b : kNoCap, stats_dev, st, p.paths));
+      return SRQ_STATUS_OK;
     }
     // both terms on the dense matrix-core kernel: one launch, the two products of a tile back to
     // back (the tile of C is still cached when the second product adds to it)

@@ -142,8 +142,9 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
     int8_t* __restrict__ Qvm, int64_t ldvm,      // transposed output [col][row], may be null
     int8_t* __restrict__ Qem, int64_t ldem,      // straight output [row][col], may be null
     uint8_t* __restrict__ mask, int64_t mask_stride,   // bytes per column of the transposed bit mask
-    int32_t* __restrict__ counts) {
+    int32_t* __restrict__ counts, RunIf run) {
   __shared__ uint32_t red[64];
+  if (!run_if_ok(run)) return;
   const int cg = threadIdx.x & 15, rb = threadIdx.x >> 4;
   const int64_t col0 = (int64_t)blockIdx.x * 64 + cg * 4;
   const int64_t row0 = (int64_t)blockIdx.y * 256 + rb * 16;
@@ -306,7 +307,9 @@ __global__ __launch_bounds__(256) void rows_resid_em_kernel(const float* __restr
                                                             const float* __restrict__ rlambda,
                                                             int8_t* __restrict__ Rem, int64_t ldem,
                                                             const float* __restrict__ thresh,
-                                                            uint8_t* __restrict__ mask, int64_t mask_stride) {
+                                                            uint8_t* __restrict__ mask, int64_t mask_stride,
+                                                            RunIf run) {
+  if (!run_if_ok(run)) return;
   const int cg = threadIdx.x & 15, rb = threadIdx.x >> 4;
   const int64_t col0 = (int64_t)blockIdx.x * 64 + cg * 4;
   const int64_t row0 = (int64_t)blockIdx.y * 256 + rb * 16;     // rows is a multiple of 16
@@ -459,14 +462,14 @@ __global__ __launch_bounds__(256) void scatter_mask_kernel(const uint64_t* __res
                                                            int64_t ldq, const int32_t* __restrict__ ptr,
                                                            int32_t* __restrict__ idx, int8_t* __restrict__ val,
                                                            int64_t capacity, int8_t* __restrict__ dense,
-                                                           int64_t ldd) {
+                                                           int64_t ldd, RunIf dense_if) {
   __shared__ int wsum[4];
   const int64_t v = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const uint64_t* mv = mask + v * words;
   const uint32_t* mv32 = reinterpret_cast<const uint32_t*>(mv);
   const int8_t* qv = Q + v * ldq;
-  int8_t* dv = dense ? dense + v * ldd : nullptr;
+  int8_t* dv = (dense && run_if_ok(dense_if)) ? dense + v * ldd : nullptr;
   const bool qvec = (reinterpret_cast<uintptr_t>(qv) & 3) == 0;
   const bool dvec = dv && (reinterpret_cast<uintptr_t>(dv) & 3) == 0;
   // chunks of 256 elements (four mask words); wave w owns chunks [c0, c1)
@@ -541,14 +544,14 @@ __global__ __launch_bounds__(256) void scatter_mask16_kernel(const uint64_t* __r
                                                              int64_t ldq, const int32_t* __restrict__ ptr,
                                                              int32_t* __restrict__ idx, int8_t* __restrict__ val,
                                                              int64_t capacity, int8_t* __restrict__ dense,
-                                                             int64_t ldd) {
+                                                             int64_t ldd, RunIf dense_if) {
   __shared__ int wsum[4];
   const int64_t v = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const uint64_t* mv = mask + v * words;
   const uint16_t* mv16 = reinterpret_cast<const uint16_t*>(mv);
   const int8_t* qv = Q + v * ldq;                        // 16-byte aligned (checked by the launcher)
-  int8_t* dv = dense ? dense + v * ldd : nullptr;        // likewise
+  int8_t* dv = (dense && run_if_ok(dense_if)) ? dense + v * ldd : nullptr;   // likewise
   const int64_t nchunks = (veclen + 1023) >> 10;
   const int64_t cpw = (nchunks + 3) >> 2;
   const int64_t c0 = w * cpw < nchunks ? w * cpw : nchunks;
@@ -716,10 +719,10 @@ bool rows_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, c
 
 hipError_t launch_rows_resid_em(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                                 const float* scale, const float* lambda, const float* rlambda, int8_t* Rem,
-                                int64_t ldem, hipStream_t st) {
+                                int64_t ldem, hipStream_t st, RunIf run) {
   dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 255) / 256));
   hipLaunchKernelGGL(rows_resid_em_kernel<false>, grid, dim3(256), 0, st, X, rows, cols, ldx, (float)qmax, trunc,
-                     scale, lambda, rlambda, Rem, ldem, nullptr, nullptr, 0);
+                     scale, lambda, rlambda, Rem, ldem, nullptr, nullptr, 0, run);
   return hipGetLastError();
 }
 
@@ -739,7 +742,7 @@ hipError_t launch_rows_mask_resid_em(const float* X, int64_t rows, int64_t cols,
   dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 255) / 256));
   hipLaunchKernelGGL(rows_resid_em_kernel<true>, grid, dim3(256), 0, st, X, rows, cols, ldx, (float)qmax, trunc,
                      scale, lambda, rlambda, Rem, ldem, thresh, reinterpret_cast<uint8_t*>(mask),
-                     mask_words(cols) * 8);
+                     mask_words(cols) * 8, kAlways);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(mask_count_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, mask, mask_words(cols),
@@ -760,7 +763,7 @@ hipError_t launch_cols_amax(const float* X, int64_t rows, int64_t cols, int64_t 
   if (rows <= 0 || cols <= 0) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsAmax>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      0.f, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, amax_bits, nullptr, 0,
-                     nullptr, 0, nullptr, 0, nullptr);
+                     nullptr, 0, nullptr, 0, nullptr, kAlways);
   return hipGetLastError();
 }
 
@@ -770,7 +773,7 @@ hipError_t launch_cols_codes(const float* X, int64_t rows, int64_t cols, int64_t
   if (rows <= 0 || cols <= 0) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsCodes>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      (float)qmax, trunc, scale, lambda, nullptr, nullptr, nullptr, nullptr, nullptr, ramax_bits,
-                     Qvm, ldvm, Qem, ldem, nullptr, 0, nullptr);
+                     Qvm, ldvm, Qem, ldem, nullptr, 0, nullptr, kAlways);
   return hipGetLastError();
 }
 
@@ -781,7 +784,7 @@ hipError_t launch_cols_codes_from_amax(const float* X, int64_t rows, int64_t col
   if (rows <= 0 || cols <= 0) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsCodes>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      (float)qmax, trunc, nullptr, nullptr, nullptr, amax_bits, scale, lambda, nullptr,
-                     ramax_bits, Qvm, ldvm, nullptr, 0, nullptr, 0, nullptr);
+                     ramax_bits, Qvm, ldvm, nullptr, 0, nullptr, 0, nullptr, kAlways);
   return hipGetLastError();
 }
 
@@ -793,17 +796,17 @@ hipError_t launch_cols_resid_from_amax(const float* X, int64_t rows, int64_t col
   if (rows <= 0 || cols <= 0) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsResid>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      (float)qmax, trunc, scale, lambda, nullptr, ramax_bits, rscale, rlambda, nullptr, nullptr,
-                     Rvm, ldvm, Rem, ldem, nullptr, 0, nullptr);
+                     Rvm, ldvm, Rem, ldem, nullptr, 0, nullptr, kAlways);
   return hipGetLastError();
 }
 
 hipError_t launch_cols_resid(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                              const float* scale, const float* lambda, const float* rlambda, int8_t* Rvm,
-                             int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st) {
+                             int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st, RunIf run) {
   if (rows <= 0 || cols <= 0 || (!Rvm && !Rem)) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsResid>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      (float)qmax, trunc, scale, lambda, rlambda, nullptr, nullptr, nullptr, nullptr, nullptr, Rvm,
-                     ldvm, Rem, ldem, nullptr, 0, nullptr);
+                     ldvm, Rem, ldem, nullptr, 0, nullptr, run);
   return hipGetLastError();
 }
 
@@ -813,7 +816,7 @@ hipError_t launch_cols_mask(const float* X, int64_t rows, int64_t cols, int64_t 
   if (rows <= 0 || cols <= 0) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsMask>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      0.f, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, thresh, nullptr, nullptr, 0,
-                     nullptr, 0, reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts);
+                     nullptr, 0, reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts, kAlways);
   return hipGetLastError();
 }
 
@@ -826,7 +829,7 @@ hipError_t launch_cols_mask_resid(const float* X, int64_t rows, int64_t cols, in
   if (rows <= 0 || cols <= 0) return hipSuccess;
   hipLaunchKernelGGL(cols_pass_kernel<kColsMaskResid>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols,
                      ldx, (float)qmax, trunc, scale, lambda, nullptr, ramax_bits, rscale, rlambda, thresh, nullptr,
-                     Rvm, ldvm, Rem, ldem, reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts);
+                     Rvm, ldvm, Rem, ldem, reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts, kAlways);
   return hipGetLastError();
 }
 
@@ -857,7 +860,7 @@ hipError_t launch_rows_mask(const float* X, int64_t rows, int64_t cols, int64_t 
 
 hipError_t launch_scatter_mask(const uint64_t* mask, int64_t nvec, int64_t veclen, const int8_t* Q, int64_t ldq,
                                const int32_t* ptr, int32_t* idx, int8_t* val, int64_t capacity, int8_t* dense,
-                               int64_t ldd, int64_t nnz_hint, hipStream_t st) {
+                               int64_t ldd, int64_t nnz_hint, hipStream_t st, RunIf dense_if) {
   if (nvec <= 0 || veclen <= 0) return hipSuccess;
   // measured at 8192 x 8192: skipping empty chunks pays below about one kept entry per 512
   const bool sparse = !dense && nnz_hint >= 0 && (double)nnz_hint * 512.0 < (double)nvec * (double)veclen;
@@ -868,18 +871,18 @@ hipError_t launch_scatter_mask(const uint64_t* mask, int64_t nvec, int64_t vecle
   if (!crowded && veclen >= 4096 && aligned16(Q) && (ldq % 16) == 0 && (!dense || (aligned16(dense) && (ldd % 16) == 0))) {
     if (sparse)
       hipLaunchKernelGGL(scatter_mask16_kernel<true>, dim3((unsigned)nvec), dim3(256), 0, st, mask,
-                         mask_words(veclen), veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd);
+                         mask_words(veclen), veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd, dense_if);
     else
       hipLaunchKernelGGL(scatter_mask16_kernel<false>, dim3((unsigned)nvec), dim3(256), 0, st, mask,
-                         mask_words(veclen), veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd);
+                         mask_words(veclen), veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd, dense_if);
     return hipGetLastError();
   }
   if (sparse) {
     hipLaunchKernelGGL(scatter_mask_kernel<true>, dim3((unsigned)nvec), dim3(256), 0, st, mask,
-                       mask_words(veclen), veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd);
+                       mask_words(veclen), veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd, dense_if);
   } else {
     hipLaunchKernelGGL(scatter_mask_kernel<false>, dim3((unsigned)nvec), dim3(256), 0, st, mask,
-                       mask_words(veclen), veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd);
+                       mask_words(veclen), veclen, Q, ldq, ptr, idx, val, capacity, dense, ldd, dense_if);
   }
   return hipGetLastError();
 }

@@ -181,8 +181,9 @@ __global__ __launch_bounds__(256) void residual_tile_kernel(
     const float* __restrict__ X, int64_t rows, int64_t cols, int64_t ldx, const float* __restrict__ scale,
     const float* __restrict__ lambda, const float* __restrict__ rlambda, float qmax, int trunc,
     int8_t* __restrict__ R_straight, int64_t ld_straight, int8_t* __restrict__ R_transposed,
-    int64_t ld_transposed) {
+    int64_t ld_transposed, RunIf run) {
   __shared__ int8_t t[kTile][kTile + 4];
+  if (!run_if_ok(run)) return;
   int64_t r0 = (int64_t)blockIdx.y * kTile, c0 = (int64_t)blockIdx.x * kTile;
   int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   int64_t c = c0 + tx;
@@ -318,15 +319,15 @@ hipError_t launch_quantize_tiles(const float* X, int64_t rows, int64_t cols, int
 hipError_t launch_residual_tiles(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
                                  const float* scale, const float* lambda, const float* rlambda,
                                  int qmax, int trunc, int8_t* R_vm, int64_t ld_vm, int8_t* R_em,
-                                 int64_t ld_em, hipStream_t st) {
+                                 int64_t ld_em, hipStream_t st, RunIf run) {
   if (rows <= 0 || cols <= 0 || (!R_vm && !R_em)) return hipSuccess;
   dim3 grid = tile_grid(rows, cols);
   if (axis == SRQ_AXIS_ROW)   // vector-major is straight, element-major is transposed
     hipLaunchKernelGGL(residual_tile_kernel<0>, grid, dim3(256), 0, st, X, rows, cols, ldx, scale, lambda,
-                       rlambda, (float)qmax, trunc, R_vm, ld_vm, R_em, ld_em);
+                       rlambda, (float)qmax, trunc, R_vm, ld_vm, R_em, ld_em, run);
   else                        // element-major is straight, vector-major is transposed
     hipLaunchKernelGGL(residual_tile_kernel<1>, grid, dim3(256), 0, st, X, rows, cols, ldx, scale, lambda,
-                       rlambda, (float)qmax, trunc, R_em, ld_em, R_vm, ld_vm);
+                       rlambda, (float)qmax, trunc, R_em, ld_em, R_vm, ld_vm, run);
   return hipGetLastError();
 }
 

@@ -176,7 +176,8 @@ __global__ __launch_bounds__(256) void densify_kernel(const int32_t* __restrict_
                                                       const int32_t* __restrict__ idx,
                                                       const int8_t* __restrict__ val, int64_t veclen,
                                                       int64_t capacity, int8_t* __restrict__ dense,
-                                                      int64_t ld) {
+                                                      int64_t ld, RunIf run) {
+  if (!run_if_ok(run)) return;
   int64_t v = blockIdx.x;
   int8_t* row = dense + v * ld;
   if ((reinterpret_cast<uintptr_t>(row) & 15) == 0) {
@@ -193,9 +194,18 @@ __global__ __launch_bounds__(256) void densify_kernel(const int32_t* __restrict_
   for (int64_t p = p0 + threadIdx.x; p < p1; p += 256) row[idx[p]] = val[p];
 }
 
-__global__ void stats_kernel(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b, int64_t cap_a,
-                             int64_t cap_b, srq_stats_t* out) {
+__global__ void decide_paths_kernel(const int64_t* nnz, int term_a, int term_b, int64_t min_a, int64_t min_b,
+                                    int32_t* paths) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
+    paths[0] = term_a ? (nnz[0] >= min_a ? 2 : 1) : 0;
+    paths[1] = term_b ? (nnz[1] >= min_b ? 2 : 1) : 0;
+  }
+}
+
+__global__ void stats_kernel(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b, int64_t cap_a,
+                             int64_t cap_b, srq_stats_t* out, const int32_t* paths_dev) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    if (paths_dev) { path_a = paths_dev[0]; path_b = paths_dev[1]; }
     const int64_t na = nnz_a ? *nnz_a : 0, nb = nnz_b ? *nnz_b : 0;
     out->nnz_a = na;
     out->nnz_b = nb;
@@ -285,16 +295,24 @@ hipError_t launch_select_scatter(const float* X, int64_t rows, int64_t cols, int
 }
 
 hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* val, int64_t nvec,
-                          int64_t veclen, int64_t capacity, int8_t* dense, int64_t ld, hipStream_t st) {
+                          int64_t veclen, int64_t capacity, int8_t* dense, int64_t ld, hipStream_t st, RunIf run) {
   if (nvec <= 0 || veclen <= 0) return hipSuccess;
   hipLaunchKernelGGL(densify_kernel, dim3((unsigned)nvec), dim3(256), 0, st, ptr, idx, val, veclen,
-                     capacity, dense, ld);
+                     capacity, dense, ld, run);
+  return hipGetLastError();
+}
+
+hipError_t launch_decide_paths(const int64_t* nnz, int term_a, int term_b, int64_t min_mfma_a, int64_t min_mfma_b,
+                               int32_t* paths, hipStream_t st) {
+  hipLaunchKernelGGL(decide_paths_kernel, dim3(1), dim3(64), 0, st, nnz, term_a, term_b, min_mfma_a, min_mfma_b,
+                     paths);
   return hipGetLastError();
 }
 
 hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b, int64_t cap_a,
-                        int64_t cap_b, srq_stats_t* out, hipStream_t st) {
-  hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(64), 0, st, nnz_a, nnz_b, path_a, path_b, cap_a, cap_b, out);
+                        int64_t cap_b, srq_stats_t* out, hipStream_t st, const int32_t* paths_dev) {
+  hipLaunchKernelGGL(stats_kernel, dim3(1), dim3(64), 0, st, nnz_a, nnz_b, path_a, path_b, cap_a, cap_b, out,
+                     paths_dev);
   return hipGetLastError();
 }
 

@@ -19,13 +19,23 @@ struct srq_context {
   hipEvent_t prof_ev[2 * SRQ_NUM_STAGES];   // start/stop per stage, created on enable
   int prof_created;
   int scale_mode;        // srq_scale_t of the next srq_compensated_gemm calls
-  int last_path_a;       // execution SRQ_STRATEGY_AUTO chose for term 1 in the previous call (0: none yet)
-  int last_path_b;       // the same for term 2
+  int last_path_a;       // execution the caller expects SRQ_STRATEGY_AUTO to pick for term 1 (srq_set_auto_hint;
+  int last_path_b;       // 0: none given, the matrix cores are assumed), resp. for term 2
 };
 
 namespace srq {
 
 inline int qmax_of_bits(int bits) { return (1 << (bits - 1)) - 1; }
+
+// A launch that only matters for some outcomes of a decision taken on the device (which execution
+// SRQ_STRATEGY_AUTO picks for a term): the kernel reads *value and does nothing unless bit *value
+// of ok_mask is set.  value == null: unconditional.
+struct RunIf {
+  const int32_t* value;
+  uint32_t ok_mask;
+};
+static __device__ __forceinline__ bool run_if_ok(const RunIf& r) { return !r.value || ((r.ok_mask >> *r.value) & 1u); }
+constexpr RunIf kAlways = {nullptr, 0u};
 
 constexpr int kSelChunk = 256;      // elements of a vector handled by one wave in count/scatter
 
@@ -57,11 +67,16 @@ struct GemmEpilogue {
   // column-block execution): when set and *run_if_nonzero == 0 the kernel does nothing
   const int32_t* run_if_nonzero;
   int dint_add;               // vector-ALU kernels: add the raw sums to D_int instead of storing them
+  // executions chosen on the device (SRQ_STRATEGY_AUTO): paths[0] / paths[1] hold the execution of
+  // term 1 / term 2; the kernel runs only if both are among those it was launched for
+  const int32_t* paths;       // device int32[2] (null: unconditional)
+  uint32_t ok_a, ok_b;        // bit p set: path p of term 1 resp. term 2 is acceptable
 };
 
 // true when the epilogue's overflow guard is set and tripped (wave-uniform: scalar loads)
 static __device__ __forceinline__ bool guard_tripped(const GemmEpilogue& ep) {
   if (ep.run_if_nonzero && *ep.run_if_nonzero == 0) return true;
+  if (ep.paths && (!((ep.ok_a >> ep.paths[0]) & 1u) || !((ep.ok_b >> ep.paths[1]) & 1u))) return true;
   return ep.guard_nnz && (ep.guard_nnz[0] > ep.guard_cap_a || ep.guard_nnz[1] > ep.guard_cap_b);
 }
 
@@ -96,7 +111,7 @@ hipError_t launch_quantize_tiles(const float* X, int64_t rows, int64_t cols, int
 hipError_t launch_residual_tiles(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
                                  const float* scale, const float* lambda, const float* rlambda,
                                  int qmax, int trunc, int8_t* R_vm, int64_t ld_vm, int8_t* R_em,
-                                 int64_t ld_em, hipStream_t st);
+                                 int64_t ld_em, hipStream_t st, RunIf run = kAlways);
 
 // selection: counts per (chunk, vector) -> offsets -> compacted arrays
 hipError_t launch_select_count(const float* X, int64_t rows, int64_t cols, int64_t ldx, int axis,
@@ -127,7 +142,7 @@ bool rows_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, c
                       const float* lambda, const float* rlambda, const int8_t* Rem, int64_t ldem);
 hipError_t launch_rows_resid_em(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                                 const float* scale, const float* lambda, const float* rlambda, int8_t* Rem,
-                                int64_t ldem, hipStream_t st);
+                                int64_t ldem, hipStream_t st, RunIf run = kAlways);
 // that pass doubling as the selection pass of the operand (mask and counts as launch_rows_mask)
 bool rows_mask_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* scale,
                            const float* lambda, const float* rlambda, const int8_t* Rem, int64_t ldem,
@@ -157,7 +172,7 @@ hipError_t launch_fill3_u32(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, ui
                             hipStream_t st);
 hipError_t launch_cols_resid(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                              const float* scale, const float* lambda, const float* rlambda, int8_t* Rvm,
-                             int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st);
+                             int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st, RunIf run = kAlways);
 hipError_t launch_cols_mask(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* thresh,
                             uint64_t* mask, int32_t* counts, hipStream_t st);
 hipError_t launch_cols_mask_resid(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
@@ -169,10 +184,10 @@ hipError_t launch_rows_mask(const float* X, int64_t rows, int64_t cols, int64_t 
                             uint64_t* mask, int32_t* counts, hipStream_t st);
 // compaction from mask + codes; dense != null also writes the vector zero-filled to dense[v*ldd + e];
 // nnz_hint: the number of kept entries if the host knows it (picks the variant for very sparse
-// operands), else -1
+// operands), else -1; dense_if: the expansion is written only if the device-side decision allows
 hipError_t launch_scatter_mask(const uint64_t* mask, int64_t nvec, int64_t veclen, const int8_t* Q, int64_t ldq,
                                const int32_t* ptr, int32_t* idx, int8_t* val, int64_t capacity, int8_t* dense,
-                               int64_t ldd, int64_t nnz_hint, hipStream_t st);
+                               int64_t ldd, int64_t nnz_hint, hipStream_t st, RunIf dense_if = kAlways);
 // two exclusive scans in one launch; a null totals pointer skips that half
 hipError_t launch_scan_pair(const int32_t* t0, int64_t n0, int32_t* p0, int64_t* z0, const int32_t* t1,
                             int64_t n1, int32_t* p1, int64_t* z1, hipStream_t st);
@@ -207,7 +222,8 @@ hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8
 
 // CSR (vector-major) -> zero-filled dense vector-major codes
 hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* val, int64_t nvec,
-                          int64_t veclen, int64_t capacity, int8_t* dense, int64_t ld, hipStream_t st);
+                          int64_t veclen, int64_t capacity, int8_t* dense, int64_t ld, hipStream_t st,
+                          RunIf run = kAlways);
 
 // VALU SpMM.  out[v, e] = sum_p val[p] * R[idx[p]*ldr + e];  side 0: C[v, e], side 1: C[e, v].
 // Vector v owns the pairs [ptr[v], ptr_end[v]); ptr_end == null means plain CSR (ptr + 1).
@@ -262,8 +278,13 @@ bool gemm_sparse24_ok(int64_t M, int64_t N, int64_t K, const Sparse24Operand& op
 hipError_t launch_gemm_i8_sparse24(int64_t M, int64_t N, int64_t K, const Sparse24Operand& op, bool trans,
                                    const Sparse24Operand* second, const GemmEpilogue& ep, hipStream_t st);
 
+// (paths_dev != null: the executions are read from the device, path_a / path_b ignored)
 hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, int path_b, int64_t cap_a,
-                        int64_t cap_b, srq_stats_t* out, hipStream_t st);
+                        int64_t cap_b, srq_stats_t* out, hipStream_t st, const int32_t* paths_dev = nullptr);
+// SRQ_STRATEGY_AUTO's choice on the device: paths[t] = 0 if term t does not exist, else the matrix
+// cores (2) if the operand keeps at least min_mfma[t] entries, else the vector ALUs (1)
+hipError_t launch_decide_paths(const int64_t* nnz, int term_a, int term_b, int64_t min_mfma_a, int64_t min_mfma_b,
+                               int32_t* paths, hipStream_t st);
 hipError_t launch_scale_only(int64_t M, int64_t N, const GemmEpilogue& ep, hipStream_t st);
 
 }  // namespace srq

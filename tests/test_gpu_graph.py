@@ -1,5 +1,5 @@
-"""A call with a fixed strategy and the density switch off enqueues kernels only (no
-allocation, no read-back, no memset node), so a caller may record it into a HIP graph.  The
+"""A call with the density switch off enqueues kernels only (no allocation, no read-back, no
+memset node; SRQ_STRATEGY_AUTO decides on the device), so a caller may record it into a HIP graph.  The
 graph is replayed several times with new operand contents and eager work in between, and
 every replay is compared with the eager call on the same operands."""
 import numpy as np
@@ -21,11 +21,12 @@ def srq():
     h.close()
 
 
-@pytest.mark.parametrize("strategy_name", ["mfma", "valu", "smfmac"])
+@pytest.mark.parametrize("strategy_name", ["mfma", "valu", "smfmac", "auto"])
 @pytest.mark.parametrize("shape", [(256, 256, 256), (1024, 768, 512)])
 def test_fixed_strategy_call_replays_from_a_graph(srq, strategy_name, shape):
     from paper_2403_06924_amd import binding as b
-    strategy = {"mfma": b.STRATEGY_CSR_MFMA, "valu": b.STRATEGY_CSR_VALU, "smfmac": b.STRATEGY_CSR_SMFMAC}[strategy_name]
+    strategy = {"mfma": b.STRATEGY_CSR_MFMA, "valu": b.STRATEGY_CSR_VALU, "smfmac": b.STRATEGY_CSR_SMFMAC,
+                "auto": b.STRATEGY_AUTO}[strategy_name]
     M, N, K = shape
     rng = np.random.default_rng(M + N + K)
     def draw():

@@ -477,14 +477,19 @@ def test_capacity_status_in_synchronising_mode(srq, b):
     srq.ws = None                                              # force a workspace sized for 1 % density
     srq.check = False
     try:
-        srq.compensated_gemm(dev(A), dev(B), 0.0, 0.0, strategy=0, max_density=0.01)
+        # the density switch (at 90 %: not reached by the half that is kept) is the synchronising mode
+        plain = o.quantized_product(A, B)
+        drow, dcol = o.abs_means(plain.D_F)
+        ta = wl.theta_for_density(A, drow, "row", 0.5)
+        tb = wl.theta_for_density(B, dcol, "col", 0.5)
+        srq.compensated_gemm(dev(A), dev(B), ta, tb, strategy=0, max_density=0.01, dense_fallback_density=0.9)
         assert srq.last_status == b.CAPACITY
     finally:
         srq.check = True
         srq.ws = None
 
 
-@pytest.mark.parametrize("strategy", [1, 2, 3])
+@pytest.mark.parametrize("strategy", [0, 1, 2, 3])
 @pytest.mark.parametrize("shape", [(128, 128, 256), (2048, 2048, 256)])
 def test_overflow_in_non_synchronising_modes(srq, b, strategy, shape):
     """A fixed strategy cannot read the counts on the host.  With a workspace sized for 1 % and a
@@ -514,6 +519,40 @@ def test_overflow_in_non_synchronising_modes(srq, b, strategy, shape):
     assert b.read_stats(stats)["overflow"] == 0
     ref = o.compensated_gemm(A, B, 0.0, alpha=0.5)
     assert o.error_rel(ref.C, host(C)) <= REL_TOL
+
+
+@pytest.mark.parametrize("shape", [(256, 384, 512), (2304, 2048, 256), (130, 257, 129)])
+@pytest.mark.parametrize("da,db,want", [(0.003, 0.05, (1, 2)), (0.05, 0.003, (2, 1)), (0.003, 0.003, (1, 1)),
+                                        (0.05, 0.05, (2, 2))])
+def test_auto_decides_on_the_device(srq, b, shape, da, db, want):
+    """SRQ_STRATEGY_AUTO without the density switch never reads anything back: the executions are
+    chosen by a kernel from the counts, per term, and every stage matches the oracle whichever
+    combination comes out and whatever the caller's hint said (right, wrong or none).  The larger
+    shape takes the persistent kernels (paired launch when both terms go to the matrix cores)."""
+    M, N, K = shape
+    A, B = wl.make_inputs("C2", M, N, K)
+    plain = o.quantized_product(A, B)
+    drow, dcol = o.abs_means(plain.D_F)
+    ta = wl.theta_for_density(A, drow, "row", da)
+    tb = wl.theta_for_density(B, dcol, "col", db)
+    outs = []
+    try:
+        for hint in ((0, 0), want, (3 - want[0], 3 - want[1])):
+            srq.set_auto_hint(*hint)
+            ref, C, st = check_against_oracle(srq, b, A, B, ta, tb, strategy=0)
+            assert (st["path_a"], st["path_b"]) == want
+            Ct, _, _ = srq.compensated_gemm(dev(A), dev(B), ta, tb, strategy=0, alpha=0.5)   # the timed configuration
+            outs.append(host(Ct))
+            assert rel_fro(np.float32(0.5) * ref.C, outs[-1]) <= REL_TOL
+    finally:
+        srq.set_auto_hint(0, 0)
+    assert (outs[0] == outs[1]).all() and (outs[0] == outs[2]).all()
+    # one term only
+    inf = float("inf")
+    ref, C, st = check_against_oracle(srq, b, A, B, ta, inf, strategy=0)
+    assert (st["path_a"], st["path_b"]) == (want[0], 0)
+    ref, C, st = check_against_oracle(srq, b, A, B, inf, tb, strategy=0)
+    assert (st["path_a"], st["path_b"]) == (0, want[1])
 
 
 def test_run_twice_is_deterministic(srq, b):
