@@ -155,9 +155,12 @@ srq_status_t srq_set_scale_mode(srq_handle_t handle, srq_scale_t mode);
  * product runs on the vector ALUs (1) or on the matrix cores (2).  Some intermediates are laid
  * out for one or the other before that decision exists; the library writes them for the execution
  * named here (0 = no expectation: the matrix cores) and, if the decision then differs, once more
- * in the other layout.  The hint never changes a result, only the time of a call; a caller
- * that reads srq_stats_t after a call can pass on path_a / path_b as the hint for the next call on
- * similar operands.  Host call. */
+ * in the other layout.  The hint never changes a result, only the time of a call.  The handle
+ * also learns by itself: the deciding kernel stores its choice into pinned host memory of the
+ * handle (a plain store from the device, no synchronisation), and the next call on the handle
+ * takes whatever it finds there as its expectation, so a sequence of calls on similar operands
+ * needs no hint after the first.  A call recorded into a HIP graph keeps storing there on every
+ * replay: the handle must outlive the graph.  Host call. */
 srq_status_t srq_set_auto_hint(srq_handle_t handle, int path_a, int path_b);
 
 /* Stage timing of srq_compensated_gemm (the per-stage time shares of Sec. 4.1.2).  When

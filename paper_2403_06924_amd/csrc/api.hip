@@ -280,7 +280,8 @@ srq_status_t srq_create(srq_handle_t* handle, int device) {
     hipError_t e = hipGetDeviceCount(&n);
     if (e != hipSuccess || device >= n) { delete c; return SRQ_STATUS_HIP_ERROR; }
     e = hipSetDevice(device);
-    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->host_nnz), 2 * sizeof(int64_t), 0);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->host_nnz), 4 * sizeof(int64_t), 0);
+    if (e == hipSuccess) c->host_nnz[2] = 0;   // (the two executions the device reported last, see seen_paths)
     int cus = 0;
     if (e == hipSuccess) e = srq::gemm_device_cus(&cus);
     if (e != hipSuccess) { delete c; return SRQ_STATUS_HIP_ERROR; }
@@ -289,6 +290,14 @@ srq_status_t srq_create(srq_handle_t* handle, int device) {
   }
   *handle = c;
   return SRQ_STATUS_OK;
+}
+
+// Two words of the handle's pinned host buffer into which the deciding kernel of SRQ_STRATEGY_AUTO
+// stores, straight from the device, the execution it chose for each term: the next call on the
+// handle reads them as its expectation without any synchronisation (whatever is there is only a
+// hint: a stale or half-updated value costs time, never a result).
+static volatile int32_t* seen_paths(srq_handle_t h) {
+  return h->host_nnz ? reinterpret_cast<volatile int32_t*>(h->host_nnz + 2) : nullptr;
 }
 
 srq_status_t srq_set_scale_mode(srq_handle_t h, srq_scale_t mode) {
@@ -301,6 +310,7 @@ srq_status_t srq_set_auto_hint(srq_handle_t h, int path_a, int path_b) {
   if (!h || path_a < 0 || path_a > 2 || path_b < 0 || path_b > 2) return SRQ_STATUS_INVALID_ARG;
   h->last_path_a = path_a;
   h->last_path_b = path_b;
+  if (volatile int32_t* seen = seen_paths(h)) { seen[0] = path_a; seen[1] = path_b; }
   return SRQ_STATUS_OK;
 }
 
@@ -717,6 +727,14 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     const int64_t nrows[6] = {M, N, M, N, M, N};
     SRQ_HIP(h, launch_zero_pad(mats, nrows, 6, K, Kc, st));
   }
+  if (strategy == SRQ_STRATEGY_AUTO && dense_fallback_density > 1.f) {
+    // where the device-side decision of the previous calls went (or the caller's hint)
+    if (volatile int32_t* seen = seen_paths(h)) {
+      const int sa = seen[0], sb = seen[1];
+      if (sa == kPathValu || sa == kPathMfma) h->last_path_a = sa;
+      if (sb == kPathValu || sb == kPathMfma) h->last_path_b = sb;
+    }
+  }
   // operand A: vectors are contiguous rows
   if (fastA) {
     // the K-contiguous residual codes of A feed the matrix-core executions of term 2; when that
@@ -867,7 +885,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       const double ca = K > 8192 ? kAutoMfmaDensityALongK : kAutoMfmaDensityA;
       const double cb = K > 8192 ? kAutoMfmaDensityBLongK : kAutoMfmaDensityB;
       SRQ_HIP(h, launch_decide_paths(p.nnz, term_a, term_b, (int64_t)ceil(ca * (double)M * (double)K),
-                                     (int64_t)ceil(cb * (double)N * (double)K), p.paths, st));
+                                     (int64_t)ceil(cb * (double)N * (double)K), p.paths,
+                                     const_cast<int32_t*>(seen_paths(h)), st));
       if (term_a) path_a = kPathOnDevice;
       if (term_b) path_b = kPathOnDevice;
     } else if (sync_mode) {

@@ -194,11 +194,17 @@ __global__ __launch_bounds__(256) void densify_kernel(const int32_t* __restrict_
   for (int64_t p = p0 + threadIdx.x; p < p1; p += 256) row[idx[p]] = val[p];
 }
 
+// seen (optional): host-visible words that receive the decision of each term that exists, for
+// the host to read whenever it next cares to
 __global__ void decide_paths_kernel(const int64_t* nnz, int term_a, int term_b, int64_t min_a, int64_t min_b,
-                                    int32_t* paths) {
+                                    int32_t* paths, int32_t* seen) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
-    paths[0] = term_a ? (nnz[0] >= min_a ? 2 : 1) : 0;
-    paths[1] = term_b ? (nnz[1] >= min_b ? 2 : 1) : 0;
+    const int pa = term_a ? (nnz[0] >= min_a ? 2 : 1) : 0;
+    const int pb = term_b ? (nnz[1] >= min_b ? 2 : 1) : 0;
+    paths[0] = pa;
+    paths[1] = pb;
+    if (seen && pa) seen[0] = pa;
+    if (seen && pb) seen[1] = pb;
   }
 }
 
@@ -303,9 +309,9 @@ hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* 
 }
 
 hipError_t launch_decide_paths(const int64_t* nnz, int term_a, int term_b, int64_t min_mfma_a, int64_t min_mfma_b,
-                               int32_t* paths, hipStream_t st) {
+                               int32_t* paths, int32_t* seen, hipStream_t st) {
   hipLaunchKernelGGL(decide_paths_kernel, dim3(1), dim3(64), 0, st, nnz, term_a, term_b, min_mfma_a, min_mfma_b,
-                     paths);
+                     paths, seen);
   return hipGetLastError();
 }
 

@@ -284,7 +284,7 @@ hipError_t launch_stats(const int64_t* nnz_a, const int64_t* nnz_b, int path_a, 
 // SRQ_STRATEGY_AUTO's choice on the device: paths[t] = 0 if term t does not exist, else the matrix
 // cores (2) if the operand keeps at least min_mfma[t] entries, else the vector ALUs (1)
 hipError_t launch_decide_paths(const int64_t* nnz, int term_a, int term_b, int64_t min_mfma_a, int64_t min_mfma_b,
-                               int32_t* paths, hipStream_t st);
+                               int32_t* paths, int32_t* seen, hipStream_t st);
 hipError_t launch_scale_only(int64_t M, int64_t N, const GemmEpilogue& ep, hipStream_t st);
 
 }  // namespace srq
