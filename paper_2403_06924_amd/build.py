@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsrq.so")
-SOURCES = ["api.hip", "quantize.hip", "fused.hip", "select.hip", "gemm.hip", "gemm_persistent.hip",
+SOURCES = ["api.hip", "quantize.hip", "fused.hip", "select.hip", "gemm.hip", "gemm_persistent.hip", "gemm_small.hip",
            "gemm_sparse24.hip", "sparse24.hip", "spmm.hip", "colblock.hip"]
 
 # -ffp-contract=off: the dequantize / residual steps are defined with one rounding per

@@ -1044,9 +1044,9 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     if (auto_dev) {
       // Every launch one of the four outcomes (vector ALUs / matrix cores per term) needs is
       // enqueued; each reads the decision and returns at once unless it is its turn:
-      //   both on the matrix cores  -> the paired launch (if the shape allows it)
       //   term t on the vector ALUs -> its sparse kernel
-      //   term t on the matrix cores, the other not (or no paired launch) -> its own dense launch
+      //   term t on the matrix cores -> its product inside the paired launch, which runs one, the
+      //   other or both of its products (where the shape allows no paired launch: a launch each)
       // The kernel of term 2 (or the pair) applies alpha / beta.
       const uint32_t kV = 1u << kPathValu, kM = 1u << kPathMfma, kAny = ~0u;
       GemmEpilogue e2 = e1;
@@ -1055,23 +1055,23 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       e2.final_scale = scale_needed;
       e1.final_scale = scale_needed && !term_b;
       e1.paths = e2.paths = p.paths;
-      const bool pair_ok = term_a && term_b && !dbg && gemm_persistent_ok(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, e1) &&
-                           gemm_persistent_ok(M, N, Kc, p.RA_int, Kc, p.Bd, Kc, e1);
+      const GemmSecond sec = {p.RA_int, p.Bd, Kc, Kc, p.s_ra, p.s_b};
+      const bool pair_ok = term_a && term_b && !dbg && gemm_pair_ok(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, sec, e1);
       {
         StageTimer tm(h, st, SRQ_STAGE_TERM1);
-        if (pair_ok) {
-          GemmEpilogue e12 = e1;
-          e12.final_scale = scale_needed;
-          e12.ok_a = kM; e12.ok_b = kM;
-          const GemmSecond sec = {p.RA_int, p.Bd, Kc, Kc, p.s_ra, p.s_b};
-          SRQ_HIP(h, launch_gemm_i8_persistent(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, e12, st, &sec));
-        }
+        // (order of the additions to C: term 1, then term 2, whoever runs them)
         if (term_a) {
           GemmEpilogue ev = e1, em = e1;
           ev.ok_a = kV; ev.ok_b = kAny;
           SRQ_HIP(h, launch_spmm_valu(0, M, N, K, p.a_ptr, nullptr, p.a_idx, p.a_val, p.cap_a, p.RB_em, N, ev, st));
-          em.ok_a = kM; em.ok_b = pair_ok ? ~kM : kAny;
-          SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, em, st));
+          em.ok_a = kM; em.ok_b = kAny;
+          if (!pair_ok) SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, em, st));
+        }
+        if (pair_ok) {
+          GemmEpilogue e12 = e1;
+          e12.final_scale = scale_needed;
+          e12.ok_a = kM; e12.ok_b = kM; e12.each_product = 1;
+          SRQ_HIP(h, launch_gemm_i8_pair(M, N, Kc, p.Ad, Kc, p.RB_int, Kc, sec, e12, st));
         }
       }
       if (term_b) {
@@ -1079,8 +1079,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
         GemmEpilogue ev = e2, em = e2;
         ev.ok_b = kV; ev.ok_a = kAny;
         SRQ_HIP(h, launch_spmm_valu(1, N, M, K, p.b_ptr, nullptr, p.b_idx, p.b_val, p.cap_b, p.RA_em, M, ev, st));
-        em.ok_b = kM; em.ok_a = pair_ok ? ~kM : kAny;
-        SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.RA_int, Kc, p.Bd, Kc, em, st));
+        em.ok_b = kM; em.ok_a = kAny;
+        if (!pair_ok) SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.RA_int, Kc, p.Bd, Kc, em, st));
       }
       if (stats_dev)
         SRQ_HIP(h, launch_stats(term_a ? p.nnz : nullptr, term_b ? p.nnz + 1 : nullptr, 0, 0, term_a ? p.cap_a : kNoCap,
@@ -1091,17 +1091,16 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // back (the tile of C is still cached when the second product adds to it)
     const int8_t* t1a = path_a == kPathMfma ? p.Ad : p.A_int;
     const int8_t* t2b = path_b == kPathMfma ? p.Bd : p.B_int;
+    const GemmSecond sec12 = {p.RA_int, t2b, Kc, Kc, p.s_ra, p.s_b};
     const bool pair = (path_a == kPathMfma || path_a == kPathDense) && (path_b == kPathMfma || path_b == kPathDense) &&
-                      !dbg && gemm_persistent_ok(M, N, Kc, t1a, Kc, p.RB_int, Kc, e1) &&
-                      gemm_persistent_ok(M, N, Kc, p.RA_int, Kc, t2b, Kc, e1);
+                      !dbg && gemm_pair_ok(M, N, Kc, t1a, Kc, p.RB_int, Kc, sec12, e1);
     // both terms in 2:4 form: one launch as well, on the sparse matrix cores
     const bool pair24 = path_a == kPath24 && path_b == kPath24;
     if (pair) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       GemmEpilogue e12 = e1;
       e12.final_scale = scale_needed;
-      const GemmSecond sec = {p.RA_int, t2b, Kc, Kc, p.s_ra, p.s_b};
-      SRQ_HIP(h, launch_gemm_i8_persistent(M, N, Kc, t1a, Kc, p.RB_int, Kc, e12, st, &sec));
+      SRQ_HIP(h, launch_gemm_i8_pair(M, N, Kc, t1a, Kc, p.RB_int, Kc, sec12, e12, st));
     } else if (pair24) {
       StageTimer tm(h, st, SRQ_STAGE_TERM1);
       GemmEpilogue e12 = e1;

@@ -380,6 +380,7 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int
   if (M <= 0 || N <= 0) return hipSuccess;
   if (gemm_persistent_ok(M, N, K, Qa, lda, Qb, ldb, ep))
     return launch_gemm_i8_persistent(M, N, K, Qa, lda, Qb, ldb, ep, st);
+  if (gemm_small_ok(M, N, K, Qa, lda, Qb, ldb, ep)) return launch_gemm_i8_small(M, N, K, Qa, lda, Qb, ldb, ep, st);
   // fast path: every 16-byte piece is aligned and inside [0,K)
   bool fast = ((reinterpret_cast<uintptr_t>(Qa) | reinterpret_cast<uintptr_t>(Qb)) & 15) == 0 &&
               (lda % 16) == 0 && (ldb % 16) == 0 && K > 0 && (K % 64) == 0;
@@ -388,6 +389,21 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int
     return launch_cfg<256, 256, 64>(M, N, K, Qa, lda, Qb, ldb, ep, fast, st);
   }
   return launch_cfg<128, 128, 64>(M, N, K, Qa, lda, Qb, ldb, ep, fast, st);
+}
+
+bool gemm_pair_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb, int64_t ldb,
+                  const GemmSecond& sec, const GemmEpilogue& ep) {
+  if (ep.mode != kGemmAccum || !sec.Qa || !sec.Qb) return false;
+  if (gemm_persistent_ok(M, N, K, Qa, lda, Qb, ldb, ep))
+    return gemm_persistent_ok(M, N, K, sec.Qa, sec.lda, sec.Qb, sec.ldb, ep);
+  return gemm_small_ok(M, N, K, Qa, lda, Qb, ldb, ep) && gemm_small_ok(M, N, K, sec.Qa, sec.lda, sec.Qb, sec.ldb, ep);
+}
+
+hipError_t launch_gemm_i8_pair(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb,
+                               int64_t ldb, const GemmSecond& sec, const GemmEpilogue& ep, hipStream_t st) {
+  if (gemm_persistent_ok(M, N, K, Qa, lda, Qb, ldb, ep))
+    return launch_gemm_i8_persistent(M, N, K, Qa, lda, Qb, ldb, ep, st, &sec);
+  return launch_gemm_i8_small(M, N, K, Qa, lda, Qb, ldb, ep, st, &sec);
 }
 
 hipError_t launch_scale_only(int64_t M, int64_t N, const GemmEpilogue& ep, hipStream_t st) {

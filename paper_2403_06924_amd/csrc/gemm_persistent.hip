@@ -57,6 +57,8 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   // then runs product 0 and product 1 of a tile back to back, so that the tile of C written by
   // the first is still in the caches when the second adds to it
   const int nprod = (MODE == kGemmAccum && sec.Qa) ? 2 : 1;
+  int p_lo, p_hi;                                   // the products this launch runs (device-side decision)
+  pair_range(ep, nprod, p_lo, p_hi);
 
   // ---- loader: wave w fetches rows 64w .. 64w+63 of each operand tile, eight rows per load.
   // Lane l of load j covers row 64w + 8j + l/8 and LDS piece l%8, which holds the logical piece
@@ -64,7 +66,7 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   // its parity.
   const int lrow = lane >> 3;
   int64_t vba = blockIdx.x, kta = 0;                // cursor of the K-tile being fetched
-  int proda = 0;                                    // ... and the product it belongs to
+  int proda = p_lo;                                 // ... and the product it belongs to
   const int8_t *pa, *pb;                            // row 64w of that K-tile in A and in B
   int64_t cur_lda = lda, cur_ldb = ldb;
   int64_t goff_a0 = 0, goff_a1 = 0, goff_b0 = 0, goff_b1 = 0;
@@ -87,13 +89,13 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
       ++kta;
       pa += BK;
       pb += BK;
-    } else if (proda + 1 < nprod) {
+    } else if (proda < p_hi) {
       ++proda;
       kta = 0;
       point();
     } else if (vba + G < total) {
       vba += G;
-      proda = 0;
+      proda = p_lo;
       kta = 0;
       point();
     }                                               // else stay on the last K-tile (harmless re-fetch)
@@ -133,7 +135,8 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   // ---- the output tile being multiplied
   int64_t vb = blockIdx.x, tile_m, tile_n;
   tile_of(vb, tiles_m, tiles_n, tile_m, tile_n);
-  float sreg_row = ep.s_row[tile_m * BM + tid], sreg_col = ep.s_col[tile_n * BN + tid];
+  float sreg_row = (p_lo ? sec.s_row : ep.s_row)[tile_m * BM + tid];
+  float sreg_col = (p_lo ? sec.s_col : ep.s_col)[tile_n * BN + tid];
 
   point();
   issue_loads(0);
@@ -154,8 +157,9 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
 
   const int64_t my_tiles = (total - blockIdx.x + G - 1) / G;
   int g = 0;                                        // parity of the K-tile stream across tiles
-  int prod = 0;                                     // product being multiplied (pairs: 0, 1, 0, 1, ...)
-  for (int64_t tile = 0; tile < my_tiles * nprod; ++tile) {
+  int prod = p_lo;                                  // product being multiplied (pairs: 0, 1, 0, 1, ...)
+  const bool two = p_lo != p_hi;
+  for (int64_t tile = 0; tile < my_tiles * (p_hi - p_lo + 1); ++tile) {
   for (int64_t kt = 0; kt < nk; ++kt, ++g) {
     const int cur = g & 1;
 #pragma unroll
@@ -280,8 +284,8 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
       __builtin_amdgcn_sched_barrier(0);
     }
     };
-    if (nprod == 2 && prod == 0) bands(std::false_type(), std::true_type());
-    else if (nprod == 2) bands(std::true_type(), std::false_type());
+    if (two && prod == 0) bands(std::false_type(), std::true_type());
+    else if (two) bands(std::true_type(), std::false_type());
     else bands(std::false_type(), std::false_type());
     if (SUMS) {
 #pragma unroll
@@ -292,17 +296,17 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
       }
     }
     // next product of this tile, or the next output tile of this workgroup
-    if (prod + 1 < nprod) {
+    if (prod < p_hi) {
       prod = 1;
       sreg_row = sec.s_row[tile_m * BM + tid];
       sreg_col = sec.s_col[tile_n * BN + tid];
     } else {
-      prod = 0;
+      prod = p_lo;
       vb += G;
       if (vb < total) {
         tile_of(vb, tiles_m, tiles_n, tile_m, tile_n);
-        sreg_row = ep.s_row[tile_m * BM + tid];
-        sreg_col = ep.s_col[tile_n * BN + tid];
+        sreg_row = (p_lo ? sec.s_row : ep.s_row)[tile_m * BM + tid];
+        sreg_col = (p_lo ? sec.s_col : ep.s_col)[tile_n * BN + tid];
       }
     }
   }

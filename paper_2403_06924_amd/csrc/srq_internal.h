@@ -71,13 +71,29 @@ struct GemmEpilogue {
   // term 1 / term 2; the kernel runs only if both are among those it was launched for
   const int32_t* paths;       // device int32[2] (null: unconditional)
   uint32_t ok_a, ok_b;        // bit p set: path p of term 1 resp. term 2 is acceptable
+  // paired launches only: the two products are decided one by one (product t runs iff the path of
+  // term t+1 is acceptable) instead of both or none; alpha / beta go with the second product only
+  int each_product;
 };
 
 // true when the epilogue's overflow guard is set and tripped (wave-uniform: scalar loads)
 static __device__ __forceinline__ bool guard_tripped(const GemmEpilogue& ep) {
   if (ep.run_if_nonzero && *ep.run_if_nonzero == 0) return true;
-  if (ep.paths && (!((ep.ok_a >> ep.paths[0]) & 1u) || !((ep.ok_b >> ep.paths[1]) & 1u))) return true;
+  if (ep.paths) {
+    const bool run_a = (ep.ok_a >> ep.paths[0]) & 1u, run_b = (ep.ok_b >> ep.paths[1]) & 1u;
+    if (ep.each_product ? !(run_a || run_b) : !(run_a && run_b)) return true;
+  }
   return ep.guard_nnz && (ep.guard_nnz[0] > ep.guard_cap_a || ep.guard_nnz[1] > ep.guard_cap_b);
+}
+
+// first and last product (0 or 1) a paired launch runs (guard_tripped has dealt with "none")
+static __device__ __forceinline__ void pair_range(const GemmEpilogue& ep, int nprod, int& lo, int& hi) {
+  lo = 0;
+  hi = nprod - 1;
+  if (nprod == 2 && ep.paths && ep.each_product) {
+    if (!((ep.ok_a >> ep.paths[0]) & 1u)) lo = 1;
+    if (!((ep.ok_b >> ep.paths[1]) & 1u)) hi = 0;
+  }
 }
 
 // Second product of a paired accumulate-mode launch of the persistent kernel: C += dequant(Qa.Qb^T)
@@ -219,6 +235,18 @@ bool gemm_persistent_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64
 hipError_t launch_gemm_i8_persistent(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
                                      const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st,
                                      const GemmSecond* second = nullptr);
+// the kernel for aligned problems with fewer than 256 tiles of 256 x 256 (gemm_small.hip); same contract
+bool gemm_small_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb, int64_t ldb,
+                   const GemmEpilogue& ep);
+hipError_t launch_gemm_i8_small(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb,
+                                int64_t ldb, const GemmEpilogue& ep, hipStream_t st,
+                                const GemmSecond* second = nullptr);
+// Both correction products in one accumulate-mode launch (first Qa.Qb^T with ep's scales, then sec):
+// possible when both products fit the same one of the two kernels above.
+bool gemm_pair_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb, int64_t ldb,
+                  const GemmSecond& sec, const GemmEpilogue& ep);
+hipError_t launch_gemm_i8_pair(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb,
+                               int64_t ldb, const GemmSecond& sec, const GemmEpilogue& ep, hipStream_t st);
 
 // CSR (vector-major) -> zero-filled dense vector-major codes
 hipError_t launch_densify(const int32_t* ptr, const int32_t* idx, const int8_t* val, int64_t nvec,
