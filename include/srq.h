@@ -165,8 +165,11 @@ srq_status_t srq_set_auto_hint(srq_handle_t handle, int path_a, int path_b);
 
 /* Stage timing of srq_compensated_gemm (the per-stage time shares of Sec. 4.1.2).  When
  * enabled, the call records a pair of HIP events on `stream` around each stage;
- * srq_profile_read waits for them and writes the milliseconds of the last call's stages
- * to ms[SRQ_NUM_STAGES] (host array; 0 for a stage that did not run). */
+ * srq_profile_read waits for them and writes to ms[SRQ_NUM_STAGES] (host array) the
+ * milliseconds per stage, summed over the calls made since the previous read (or since
+ * enabling): read after every call for the times of that call, or after a run of calls issued
+ * back to back for their totals without a wait in between.  The events of the last 64 calls
+ * are kept; earlier ones are forgotten.  0 for a stage that did not run. */
 enum {
   SRQ_STAGE_QUANTIZE = 0,   /* amax, scales, codes of A and B, max |residual|             */
   SRQ_STAGE_GEMM = 1,       /* INT8 product, dequantization, partial sums of |D_F|        */

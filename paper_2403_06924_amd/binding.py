@@ -196,7 +196,8 @@ class Srq:
         self._ret(self.lib.srq_profile_enable(self.h, 1 if on else 0), "srq_profile_enable")
 
     def profile_read(self):
-        """Milliseconds per stage of the last compensated_gemm call (waits for its events)."""
+        """Milliseconds per stage, summed over the compensated_gemm calls since the previous read
+        (at most the last 64); waits for their events."""
         ms = (C.c_float * len(STAGES))()
         self._ret(self.lib.srq_profile_read(self.h, ms), "srq_profile_read")
         return dict(zip(STAGES, [float(x) for x in ms]))

@@ -229,18 +229,20 @@ srq_status_t check_common(srq_handle_t h, int bits) {
 
 bool k_overflows(int64_t K, int qmax) { return K * (int64_t)qmax * qmax >= (1LL << 31); }
 
+constexpr int kProfRing = 64;   // (the size of the arrays in the handle)
+
 struct StageTimer {
   srq_handle_t h;
   hipStream_t st;
   int id;
   StageTimer(srq_handle_t h_, hipStream_t st_, int id_) : h(h_), st(st_), id(id_) {
     if (h->prof_enabled) {
-      (void)hipEventRecord(h->prof_ev[2 * id], st);
-      h->prof_used |= 1u << id;
+      (void)hipEventRecord(h->prof_ev[h->prof_slot][2 * id], st);
+      h->prof_used[h->prof_slot] |= 1u << id;
     }
   }
   ~StageTimer() {
-    if (h->prof_enabled) (void)hipEventRecord(h->prof_ev[2 * id + 1], st);
+    if (h->prof_enabled) (void)hipEventRecord(h->prof_ev[h->prof_slot][2 * id + 1], st);
   }
 };
 
@@ -319,30 +321,39 @@ srq_status_t srq_profile_enable(srq_handle_t h, int enable) {
   if (enable && !h->prof_created) {
     srq_status_t s = bind_device(h);
     if (s) return s;
-    for (int i = 0; i < 2 * SRQ_NUM_STAGES; ++i) SRQ_HIP(h, hipEventCreate(&h->prof_ev[i]));
+    for (int r = 0; r < kProfRing; ++r)
+      for (int i = 0; i < 2 * SRQ_NUM_STAGES; ++i) SRQ_HIP(h, hipEventCreate(&h->prof_ev[r][i]));
     h->prof_created = 1;
   }
   h->prof_enabled = enable ? 1 : 0;
-  h->prof_used = 0;
+  h->prof_calls = 0;
   return SRQ_STATUS_OK;
 }
 
 srq_status_t srq_profile_read(srq_handle_t h, float* ms) {
   if (!h || !ms) return SRQ_STATUS_INVALID_ARG;
-  for (int i = 0; i < SRQ_NUM_STAGES; ++i) {
-    ms[i] = 0.f;
-    if (h->prof_created && (h->prof_used & (1u << i))) {
-      SRQ_HIP(h, hipEventSynchronize(h->prof_ev[2 * i + 1]));
-      SRQ_HIP(h, hipEventElapsedTime(&ms[i], h->prof_ev[2 * i], h->prof_ev[2 * i + 1]));
+  for (int i = 0; i < SRQ_NUM_STAGES; ++i) ms[i] = 0.f;
+  if (!h->prof_created) return SRQ_STATUS_OK;
+  const int64_t n = h->prof_calls < kProfRing ? h->prof_calls : kProfRing;
+  for (int64_t c = h->prof_calls - n; c < h->prof_calls; ++c) {
+    const int r = (int)(c % kProfRing);
+    for (int i = 0; i < SRQ_NUM_STAGES; ++i) {
+      if (!(h->prof_used[r] & (1u << i))) continue;
+      float t = 0.f;
+      SRQ_HIP(h, hipEventSynchronize(h->prof_ev[r][2 * i + 1]));
+      SRQ_HIP(h, hipEventElapsedTime(&t, h->prof_ev[r][2 * i], h->prof_ev[r][2 * i + 1]));
+      ms[i] += t;
     }
   }
+  h->prof_calls = 0;
   return SRQ_STATUS_OK;
 }
 
 srq_status_t srq_destroy(srq_handle_t h) {
   if (!h) return SRQ_STATUS_INVALID_ARG;
   if (h->prof_created)
-    for (int i = 0; i < 2 * SRQ_NUM_STAGES; ++i) (void)hipEventDestroy(h->prof_ev[i]);
+    for (int r = 0; r < kProfRing; ++r)
+      for (int i = 0; i < 2 * SRQ_NUM_STAGES; ++i) (void)hipEventDestroy(h->prof_ev[r][i]);
   if (h->host_nnz) (void)hipHostFree(h->host_nnz);
   delete h;
   return SRQ_STATUS_OK;
@@ -709,7 +720,11 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   im.ld_codes = Kc;
   im.A_int = p.A_int; im.B_int = p.B_int; im.s_a = p.s_a; im.lam_a = p.lam_a; im.s_b = p.s_b; im.lam_b = p.lam_b;
 
-  h->prof_used = 0;
+  if (h->prof_enabled) {
+    h->prof_slot = (int)(h->prof_calls % kProfRing);
+    h->prof_used[h->prof_slot] = 0;
+    ++h->prof_calls;
+  }
   // the one-pass kernels derive each vector's scale from the data they hold; a matrix-wide
   // scale needs all maxima first and takes the staged kernels
   const bool global_scale = h->scale_mode == SRQ_SCALE_GLOBAL;

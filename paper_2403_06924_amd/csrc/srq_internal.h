@@ -15,8 +15,11 @@ struct srq_context {
   int64_t* host_nnz;     // pinned host buffer for the two counters read back in synchronising modes
   srq_intermediates_t last;
   int prof_enabled;
-  unsigned prof_used;                       // bit i: stage i ran in the last call
-  hipEvent_t prof_ev[2 * SRQ_NUM_STAGES];   // start/stop per stage, created on enable
+  // stage events of the last kProfRing calls (slot = call number mod kProfRing)
+  unsigned prof_used[64];                   // bit i: stage i ran in that call
+  hipEvent_t prof_ev[64][2 * SRQ_NUM_STAGES];   // start/stop per stage, created on enable
+  int prof_slot;                            // slot of the call being recorded
+  int64_t prof_calls;                       // calls recorded since the last read
   int prof_created;
   int scale_mode;        // srq_scale_t of the next srq_compensated_gemm calls
   int last_path_a;       // execution the caller expects SRQ_STRATEGY_AUTO to pick for term 1 (srq_set_auto_hint;

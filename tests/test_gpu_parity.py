@@ -555,6 +555,32 @@ def test_auto_decides_on_the_device(srq, b, shape, da, db, want):
     assert (st["path_a"], st["path_b"]) == (0, want[1])
 
 
+def test_stage_timers_sum_over_calls(srq, b):
+    """srq_profile_read returns the stage times summed over the calls since the previous read,
+    without the library waiting between those calls."""
+    A, B = wl.make_inputs("C2", 256, 256, 256)
+    Ad, Bd = dev(A), dev(B)
+    srq.profile_enable(True)
+    try:
+        for _ in range(3):                                                  # (the first calls are cold)
+            srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
+        srq.profile_read()
+        srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
+        one = srq.profile_read()
+        assert one["quantize"] > 0 and one["gemm"] > 0 and one["select"] > 0 and one["term1"] > 0
+        for _ in range(5):
+            srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
+        five = srq.profile_read()
+        assert all(five[k] > 2.0 * one[k] for k in ("quantize", "gemm", "select")), (one, five)
+        assert all(v == 0.0 for v in srq.profile_read().values())          # nothing since the last read
+        for _ in range(70):                                                 # more than the ring holds
+            srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
+        many = srq.profile_read()
+        assert 0 < many["gemm"] < 64 * 4.0 * max(one["gemm"], five["gemm"] / 5)
+    finally:
+        srq.profile_enable(False)
+
+
 def test_run_twice_is_deterministic(srq, b):
     A, B = wl.make_inputs("C3", 300, 260, 512)
     Ad, Bd = dev(A), dev(B)
