@@ -280,15 +280,16 @@ srq_status_t srq_spmm_accumulate(srq_handle_t handle, srq_axis_t side, srq_strat
  *                      quantized GEMM.  0 keeps every non-zero entry: dense compensation.
  *   dense_fallback_density   Algorithm 1's limit "s": a term whose reduced operand has
  *                      density >= s runs as a dense product on the UNREDUCED codes.  Values
- *                      > 1 switch the branch off.  Any value <= 1 makes the call synchronise
- *                      once on `stream` to read the densities (the only synchronising mode).
+ *                      > 1 switch the branch off; values <= 0 send every term to the dense
+ *                      branch.  A value in (0, 1] makes the call synchronise once on `stream`
+ *                      to read the densities (the only synchronising mode).
  *   Cin                read only if beta != 0 (ldcin >= N); must not overlap C.
  *   stats_dev          device srq_stats_t, may be NULL.
  *   dbg                host pointer to a struct of device buffers, may be NULL.
  * An operand that is reduced (finite theta) must have fewer than 2^31 elements (INT32 row
  * pointers): SRQ_STATUS_UNSUPPORTED otherwise.
  * With dbg != NULL a CSR_SMFMAC term runs as CSR_MFMA (the 2:4 kernel has no raw-sum output).
- * With dense_fallback_density > 1 the call only enqueues kernels on `stream`, whatever the
+ * With dense_fallback_density > 1 or <= 0 the call only enqueues kernels on `stream`, whatever the
  * strategy (SRQ_STRATEGY_AUTO takes its decision on the device): no allocation, no host
  * read-back, no memset node, so it may be recorded into a HIP graph by a capturing caller (the
  * workspace must be attached before).  srq_get_intermediates then reports only what exists

@@ -841,8 +841,10 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // Only the density switch needs the counts on the host.  SRQ_STRATEGY_AUTO without it decides on
     // the device: a small kernel turns the counts into an execution per term, and every launch
     // that belongs to one outcome only checks that decision itself and does nothing otherwise.
-    const bool sync_mode = dense_fallback_density <= 1.f;
-    const bool auto_dev = strategy == SRQ_STRATEGY_AUTO && !sync_mode;
+    // (a limit <= 0 is reached by any density, including none kept: the dense branch needs no count)
+    const bool always_dense = dense_fallback_density <= 0.f;
+    const bool sync_mode = dense_fallback_density <= 1.f && !always_dense;
+    const bool auto_dev = strategy == SRQ_STRATEGY_AUTO && !sync_mode && !always_dense;
     const RunIf a_on_mfma = {p.paths + 0, 1u << kPathMfma}, a_on_valu = {p.paths + 0, 1u << kPathValu};
     const RunIf b_on_mfma = {p.paths + 1, 1u << kPathMfma}, b_on_valu = {p.paths + 1, 1u << kPathValu};
     // the reduced operands in 2:4 form with the dense residual codes they are multiplied with
@@ -930,8 +932,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
         return SRQ_STATUS_CAPACITY;
       }
     } else {
-      if (term_a) path_a = strategy_path(strategy);
-      if (term_b) path_b = strategy_path(strategy);
+      if (term_a) path_a = always_dense ? kPathDense : strategy_path(strategy);
+      if (term_b) path_b = always_dense ? kPathDense : strategy_path(strategy);
     }
     // the 2:4 kernel needs whole 256 x 256 tiles of C and cannot write the raw sums the debug
     // block asks for: such a term takes the plain matrix-core path

@@ -123,13 +123,18 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
 }
 
 // ---- operand with strided vectors (B, columns of a row-major matrix) ------------------------
-// A block covers 256 rows x 64 columns; thread (cg, rb) holds rows rb*16..rb*16+15 of the four
-// columns cg*4..cg*4+3.
+// A block of 256 threads covers (256 / CG * 16) rows x (4 * CG) columns; thread (cg, rb) holds rows
+// rb*16..rb*16+15 of the four columns cg*4..cg*4+3.  CG sets the shape: the wider the block, the
+// longer the contiguous piece of a row that one load instruction of a wave fetches (16 * CG bytes,
+// up to 1 KiB), the shorter the contiguous piece of a column of transposed codes a block writes.
 // (kColsMaskResid: the selection pass also writes the residual codes, so that B is read three
 // times per call and not four)
+constexpr int kCgAmax = 16, kCgMask = 8, kCgCodes = 8;   // (measured at 8192^2: 8 beats 16 by 3 % in the passes that write codes, 4 and 32 lose 15 %)
 enum ColsMode { kColsAmax = 0, kColsCodes = 1, kColsResid = 2, kColsMask = 3, kColsMaskResid = 4 };
 constexpr bool cols_resid(int mode) { return mode == kColsResid || mode == kColsMaskResid; }
 constexpr bool cols_mask(int mode) { return mode == kColsMask || mode == kColsMaskResid; }
+// column groups per block of each pass (powers of two, 16..64)
+constexpr int cols_cg(int mode) { return mode == kColsAmax ? kCgAmax : mode == kColsMask ? kCgMask : kCgCodes; }
 
 template <int MODE>
 __global__ __launch_bounds__(256) void cols_pass_kernel(
@@ -143,14 +148,15 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
     int8_t* __restrict__ Qem, int64_t ldem,      // straight output [row][col], may be null
     uint8_t* __restrict__ mask, int64_t mask_stride,   // bytes per column of the transposed bit mask
     int32_t* __restrict__ counts, RunIf run) {
-  __shared__ uint32_t red[64];
+  constexpr int CG = cols_cg(MODE), BC = 4 * CG, BR = 256 / CG * 16;   // block: BR rows x BC columns
+  __shared__ uint32_t red[BC];
   if (!run_if_ok(run)) return;
-  const int cg = threadIdx.x & 15, rb = threadIdx.x >> 4;
-  const int64_t col0 = (int64_t)blockIdx.x * 64 + cg * 4;
-  const int64_t row0 = (int64_t)blockIdx.y * 256 + rb * 16;
+  const int cg = threadIdx.x & (CG - 1), rb = threadIdx.x / CG;
+  const int64_t col0 = (int64_t)blockIdx.x * BC + cg * 4;
+  const int64_t row0 = (int64_t)blockIdx.y * BR + rb * 16;
   const bool colok = col0 < cols;                 // cols is a multiple of 4
   if (MODE != kColsResid) {
-    if (threadIdx.x < 64) red[threadIdx.x] = 0;
+    if (threadIdx.x < BC) red[threadIdx.x] = 0;
     __syncthreads();
   }
   float4 v[16];
@@ -172,8 +178,8 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
 #pragma unroll
     for (int c = 0; c < 4; ++c) atomicMax(&red[cg * 4 + c], __float_as_uint(m[c]));
     __syncthreads();
-    if (threadIdx.x < 64) {
-      int64_t col = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (threadIdx.x < BC) {
+      int64_t col = (int64_t)blockIdx.x * BC + threadIdx.x;
       if (col < cols) atomicMax(&amax_bits[col], red[threadIdx.x]);
     }
     return;
@@ -198,8 +204,8 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
     for (int c = 0; c < 4; ++c)
       if (bits[c]) atomicAdd(&red[cg * 4 + c], (uint32_t)__popc(bits[c]));
     __syncthreads();
-    if (threadIdx.x < 64) {
-      int64_t col = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (threadIdx.x < BC) {
+      int64_t col = (int64_t)blockIdx.x * BC + threadIdx.x;
       if (col < cols && red[threadIdx.x]) atomicAdd(&counts[col], (int32_t)red[threadIdx.x]);
     }
     if (MODE == kColsMask) return;
@@ -286,8 +292,8 @@ __global__ __launch_bounds__(256) void cols_pass_kernel(
 #pragma unroll
     for (int c = 0; c < 4; ++c) atomicMax(&red[cg * 4 + c], __float_as_uint(rm[c]));
     __syncthreads();
-    if (threadIdx.x < 64) {
-      int64_t col = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (threadIdx.x < BC) {
+      int64_t col = (int64_t)blockIdx.x * BC + threadIdx.x;
       if (col < cols) atomicMax(&amax_bits[col], red[threadIdx.x]);
     }
   }
@@ -754,14 +760,15 @@ bool cols_pass_ok(const float* X, int64_t cols, int64_t ldx) {
   return cols > 0 && (cols % 4) == 0 && (ldx % 4) == 0 && aligned16(X);
 }
 
-static dim3 cols_grid(int64_t rows, int64_t cols) {
-  return dim3((unsigned)((cols + 63) / 64), (unsigned)((rows + 255) / 256));
+static dim3 cols_grid(int mode, int64_t rows, int64_t cols) {
+  const int bc = 4 * cols_cg(mode), br = 256 / cols_cg(mode) * 16;
+  return dim3((unsigned)((cols + bc - 1) / bc), (unsigned)((rows + br - 1) / br));
 }
 
 hipError_t launch_cols_amax(const float* X, int64_t rows, int64_t cols, int64_t ldx, uint32_t* amax_bits,
                             hipStream_t st) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
-  hipLaunchKernelGGL(cols_pass_kernel<kColsAmax>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+  hipLaunchKernelGGL(cols_pass_kernel<kColsAmax>, cols_grid(kColsAmax, rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      0.f, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, amax_bits, nullptr, 0,
                      nullptr, 0, nullptr, 0, nullptr, kAlways);
   return hipGetLastError();
@@ -771,7 +778,7 @@ hipError_t launch_cols_codes(const float* X, int64_t rows, int64_t cols, int64_t
                              const float* scale, const float* lambda, int8_t* Qvm, int64_t ldvm, int8_t* Qem,
                              int64_t ldem, uint32_t* ramax_bits, hipStream_t st) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
-  hipLaunchKernelGGL(cols_pass_kernel<kColsCodes>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+  hipLaunchKernelGGL(cols_pass_kernel<kColsCodes>, cols_grid(kColsCodes, rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      (float)qmax, trunc, scale, lambda, nullptr, nullptr, nullptr, nullptr, nullptr, ramax_bits,
                      Qvm, ldvm, Qem, ldem, nullptr, 0, nullptr, kAlways);
   return hipGetLastError();
@@ -782,7 +789,7 @@ hipError_t launch_cols_codes_from_amax(const float* X, int64_t rows, int64_t col
                                        int trunc, const uint32_t* amax_bits, float* scale, float* lambda,
                                        int8_t* Qvm, int64_t ldvm, uint32_t* ramax_bits, hipStream_t st) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
-  hipLaunchKernelGGL(cols_pass_kernel<kColsCodes>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+  hipLaunchKernelGGL(cols_pass_kernel<kColsCodes>, cols_grid(kColsCodes, rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      (float)qmax, trunc, nullptr, nullptr, nullptr, amax_bits, scale, lambda, nullptr,
                      ramax_bits, Qvm, ldvm, nullptr, 0, nullptr, 0, nullptr, kAlways);
   return hipGetLastError();
@@ -794,7 +801,7 @@ hipError_t launch_cols_resid_from_amax(const float* X, int64_t rows, int64_t col
                                        const uint32_t* ramax_bits, float* rscale, float* rlambda, int8_t* Rvm,
                                        int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
-  hipLaunchKernelGGL(cols_pass_kernel<kColsResid>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+  hipLaunchKernelGGL(cols_pass_kernel<kColsResid>, cols_grid(kColsResid, rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      (float)qmax, trunc, scale, lambda, nullptr, ramax_bits, rscale, rlambda, nullptr, nullptr,
                      Rvm, ldvm, Rem, ldem, nullptr, 0, nullptr, kAlways);
   return hipGetLastError();
@@ -804,7 +811,7 @@ hipError_t launch_cols_resid(const float* X, int64_t rows, int64_t cols, int64_t
                              const float* scale, const float* lambda, const float* rlambda, int8_t* Rvm,
                              int64_t ldvm, int8_t* Rem, int64_t ldem, hipStream_t st, RunIf run) {
   if (rows <= 0 || cols <= 0 || (!Rvm && !Rem)) return hipSuccess;
-  hipLaunchKernelGGL(cols_pass_kernel<kColsResid>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+  hipLaunchKernelGGL(cols_pass_kernel<kColsResid>, cols_grid(kColsResid, rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      (float)qmax, trunc, scale, lambda, rlambda, nullptr, nullptr, nullptr, nullptr, nullptr, Rvm,
                      ldvm, Rem, ldem, nullptr, 0, nullptr, run);
   return hipGetLastError();
@@ -814,7 +821,7 @@ hipError_t launch_cols_resid(const float* X, int64_t rows, int64_t cols, int64_t
 hipError_t launch_cols_mask(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* thresh,
                             uint64_t* mask, int32_t* counts, hipStream_t st) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
-  hipLaunchKernelGGL(cols_pass_kernel<kColsMask>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
+  hipLaunchKernelGGL(cols_pass_kernel<kColsMask>, cols_grid(kColsMask, rows, cols), dim3(256), 0, st, X, rows, cols, ldx,
                      0.f, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, thresh, nullptr, nullptr, 0,
                      nullptr, 0, reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts, kAlways);
   return hipGetLastError();
@@ -827,7 +834,7 @@ hipError_t launch_cols_mask_resid(const float* X, int64_t rows, int64_t cols, in
                                   int64_t ldem, const float* thresh, uint64_t* mask, int32_t* counts,
                                   hipStream_t st) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
-  hipLaunchKernelGGL(cols_pass_kernel<kColsMaskResid>, cols_grid(rows, cols), dim3(256), 0, st, X, rows, cols,
+  hipLaunchKernelGGL(cols_pass_kernel<kColsMaskResid>, cols_grid(kColsMaskResid, rows, cols), dim3(256), 0, st, X, rows, cols,
                      ldx, (float)qmax, trunc, scale, lambda, nullptr, ramax_bits, rscale, rlambda, thresh, nullptr,
                      Rvm, ldvm, Rem, ldem, reinterpret_cast<uint8_t*>(mask), mask_words(rows) * 8, counts, kAlways);
   return hipGetLastError();

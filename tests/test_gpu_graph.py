@@ -21,12 +21,14 @@ def srq():
     h.close()
 
 
-@pytest.mark.parametrize("strategy_name", ["mfma", "valu", "smfmac", "auto"])
+@pytest.mark.parametrize("strategy_name", ["mfma", "valu", "smfmac", "auto", "dense"])
 @pytest.mark.parametrize("shape", [(256, 256, 256), (1024, 768, 512)])
 def test_fixed_strategy_call_replays_from_a_graph(srq, strategy_name, shape):
     from paper_2403_06924_amd import binding as b
     strategy = {"mfma": b.STRATEGY_CSR_MFMA, "valu": b.STRATEGY_CSR_VALU, "smfmac": b.STRATEGY_CSR_SMFMAC,
-                "auto": b.STRATEGY_AUTO}[strategy_name]
+                "auto": b.STRATEGY_AUTO, "dense": b.STRATEGY_AUTO}[strategy_name]
+    # "dense": every term on the dense branch of Algorithm 1 line 11 (limit 0), which needs no count on the host
+    kw = dict(strategy=strategy, max_density=1.0, dense_fallback_density=0.0 if strategy_name == "dense" else 2.0)
     M, N, K = shape
     rng = np.random.default_rng(M + N + K)
     def draw():
@@ -41,12 +43,12 @@ def test_fixed_strategy_call_replays_from_a_graph(srq, strategy_name, shape):
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):                        # warm-up on the capture stream
-        srq.compensated_gemm(Ad, Bd, theta, theta, strategy=strategy, out=Cg, stats=stats, max_density=1.0)
+        srq.compensated_gemm(Ad, Bd, theta, theta, out=Cg, stats=stats, **kw)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
-        srq.compensated_gemm(Ad, Bd, theta, theta, strategy=strategy, out=Cg, stats=stats, max_density=1.0)
+        srq.compensated_gemm(Ad, Bd, theta, theta, out=Cg, stats=stats, **kw)
     for _ in range(3):
         A2, B2 = draw()
         Ad.copy_(A2); Bd.copy_(B2)
@@ -58,7 +60,7 @@ def test_fixed_strategy_call_replays_from_a_graph(srq, strategy_name, shape):
         st_graph = b.read_stats(stats)
         Ce = torch.empty_like(Cg)
         stats_e = b.stats_tensor()
-        srq.compensated_gemm(A2, B2, theta, theta, strategy=strategy, out=Ce, stats=stats_e, max_density=1.0)
+        srq.compensated_gemm(A2, B2, theta, theta, out=Ce, stats=stats_e, **kw)
         torch.cuda.synchronize()
         st_eager = b.read_stats(stats_e)
         assert st_graph["nnz_a"] == st_eager["nnz_a"] > 0 and st_graph["nnz_b"] == st_eager["nnz_b"] > 0
