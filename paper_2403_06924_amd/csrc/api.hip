@@ -750,6 +750,11 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
       if (sb == kPathValu || sb == kPathMfma) h->last_path_b = sb;
     }
   }
+  // the two vectors of column maxima and the per-column counts of the selection that B's passes
+  // accumulate into start at zero
+  const ClearList b_clear = {p.amax_b, N, comp ? p.ramax_b : nullptr, N,
+                             (comp && term_b) ? reinterpret_cast<uint32_t*>(p.tot_b) : nullptr, N};
+  bool b_cleared = false;
   // operand A: vectors are contiguous rows
   if (fastA) {
     // the K-contiguous residual codes of A feed the matrix-core executions of term 2; when that
@@ -760,9 +765,11 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
                              (strategy == SRQ_STRATEGY_AUTO && h->last_path_b == kPathValu));
     // (SRQ_STRATEGY_AUTO goes by the caller's hint, srq_set_auto_hint; a wrong or missing hint only
     // costs the pass that writes the other layout once the decision is known)
+    // (this launch also zeroes what B's passes accumulate into, see below)
+    b_cleared = fastB && rows_fused_can_clear(M, b_clear);
     SRQ_HIP(h, launch_rows_fused(A, M, K, lda, qmax, trunc, p.A_int, Kc, p.s_a, p.lam_a,
                                  (comp && !skip_ra_vm) ? p.RA_int : nullptr, Kc, comp ? p.s_ra : nullptr,
-                                 comp ? p.lam_ra : nullptr, st));
+                                 comp ? p.lam_ra : nullptr, st, nullptr, nullptr, b_cleared ? &b_clear : nullptr));
     ra_vm_done = comp && !skip_ra_vm;
   } else {
     SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_a), M, 0, st));
@@ -777,10 +784,9 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   }
   // operand B: vectors are the columns of a row-major matrix; codes are stored transposed
   if (fastB) {
-    // one launch clears the two vectors of maxima and the per-column counts of the selection;
-    // the code and residual passes derive the scales from the maxima themselves
-    SRQ_HIP(h, launch_fill3_u32(p.amax_b, N, comp ? p.ramax_b : nullptr, N,
-                                (comp && term_b) ? reinterpret_cast<uint32_t*>(p.tot_b) : nullptr, N, st));
+    // (cleared by A's pass where that ran, else by a launch of its own); the code and residual
+    // passes derive the scales from the maxima themselves
+    if (!b_cleared) SRQ_HIP(h, launch_fill3_u32(b_clear.a, b_clear.na, b_clear.b, b_clear.nb, b_clear.c, b_clear.nc, st));
     SRQ_HIP(h, launch_cols_amax(B, K, N, ldb, p.amax_b, st));
     SRQ_HIP(h, launch_cols_codes_from_amax(B, K, N, ldb, qmax, trunc, p.amax_b, p.s_b, p.lam_b, p.B_int, Kc,
                                            comp ? p.ramax_b : nullptr, st));
@@ -836,6 +842,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.A_int, Kc, p.B_int, Kc, ep, st));
   }
   int path_a = 0, path_b = 0;
+  bool decide_in_scan = false;                 // SRQ_STRATEGY_AUTO's decision and the statistics come from the scan kernel
   if (comp) {
     // line 9 and the branch of line 11 need the counts on the host in these modes
     // Only the density switch needs the counts on the host.  SRQ_STRATEGY_AUTO without it decides on
@@ -892,18 +899,26 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
         SRQ_HIP(h, launch_select_scan(p.cnt_b, N, chk, p.tot_b, p.b_ptr, p.nnz + 1, st));
       }
     }
+    // line 9 and the branch of line 11: which execution each term takes.  SRQ_STRATEGY_AUTO: decided
+    // on the device, by the scan kernel itself where it scans both operands (it then also writes
+    // the statistics), else by a kernel of its own.
+    // (for K > 8192 the K x 512-byte slab of codes an XCD gathers from outgrows its L2 and the
+    // vector-ALU kernel loses earlier: measured crossover 0.8 % at 16384^3)
+    const int64_t min_mfma_a =
+        (int64_t)ceil((K > 8192 ? kAutoMfmaDensityALongK : kAutoMfmaDensityA) * (double)M * (double)K);
+    const int64_t min_mfma_b =
+        (int64_t)ceil((K > 8192 ? kAutoMfmaDensityBLongK : kAutoMfmaDensityB) * (double)N * (double)K);
+    decide_in_scan = auto_dev && (!term_b || fastB);
+    const ScanDecision dec = {p.paths, const_cast<int32_t*>(seen_paths(h)), min_mfma_a, min_mfma_b, stats_dev,
+                              term_a ? p.cap_a : kNoCap, term_b ? p.cap_b : kNoCap};
     SRQ_HIP(h, launch_scan_pair(term_a ? p.tot_a : nullptr, M, p.a_ptr, p.nnz + 0,
-                                (term_b && fastB) ? p.tot_b : nullptr, N, p.b_ptr, p.nnz + 1, st));
-    // line 9 and the branch of line 11: which execution each term takes
+                                (term_b && fastB) ? p.tot_b : nullptr, N, p.b_ptr, p.nnz + 1, st,
+                                decide_in_scan ? &dec : nullptr));
     int64_t known_a = -1, known_b = -1;        // kept entries, once the host has read them
     if (auto_dev) {
-      // (for K > 8192 the K x 512-byte slab of codes an XCD gathers from outgrows its L2 and the
-      // vector-ALU kernel loses earlier: measured crossover 0.8 % at 16384^3)
-      const double ca = K > 8192 ? kAutoMfmaDensityALongK : kAutoMfmaDensityA;
-      const double cb = K > 8192 ? kAutoMfmaDensityBLongK : kAutoMfmaDensityB;
-      SRQ_HIP(h, launch_decide_paths(p.nnz, term_a, term_b, (int64_t)ceil(ca * (double)M * (double)K),
-                                     (int64_t)ceil(cb * (double)N * (double)K), p.paths,
-                                     const_cast<int32_t*>(seen_paths(h)), st));
+      if (!decide_in_scan)
+        SRQ_HIP(h, launch_decide_paths(p.nnz, term_a, term_b, min_mfma_a, min_mfma_b, p.paths,
+                                       const_cast<int32_t*>(seen_paths(h)), st));
       if (term_a) path_a = kPathOnDevice;
       if (term_b) path_b = kPathOnDevice;
     } else if (sync_mode) {
@@ -1099,7 +1114,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
         em.ok_b = kM; em.ok_a = kAny;
         if (!pair_ok) SRQ_HIP(h, launch_gemm_i8(M, N, Kc, p.RA_int, Kc, p.Bd, Kc, em, st));
       }
-      if (stats_dev)
+      if (stats_dev && !decide_in_scan)
         SRQ_HIP(h, launch_stats(term_a ? p.nnz : nullptr, term_b ? p.nnz + 1 : nullptr, 0, 0, term_a ? p.cap_a : kNoCap,
                                 term_b ? p.cap_b : kNoCap, stats_dev, st, p.paths));
       return SRQ_STATUS_OK;

@@ -18,6 +18,7 @@
 //                       when the vector ALUs will run the second term
 //                       (rows_resid_em_kernel<true>).
 //   scatter_mask_kernel compaction to CSR / CSC from the bit mask and the INT8 codes.
+#include <cstring>
 #include "srq_internal.h"
 
 namespace srq {
@@ -64,8 +65,18 @@ __global__ __launch_bounds__(256) void rows_fused_kernel(const float* __restrict
                                                          // from here instead of from its maximum (and not
                                                          // written back)
                                                          const float* __restrict__ given_scale,
-                                                         const float* __restrict__ given_lambda) {
+                                                         const float* __restrict__ given_lambda,
+                                                         // words this launch zeroes on the side (one per
+                                                         // thread and array), so that the kernels after it
+                                                         // need no launch to clear their accumulators
+                                                         ClearList clr) {
   __shared__ float sm[4];
+  {
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (clr.a && g < clr.na) clr.a[g] = 0u;
+    if (clr.b && g < clr.nb) clr.b[g] = 0u;
+    if (clr.c && g < clr.nc) clr.c[g] = 0u;
+  }
   const int64_t row = blockIdx.x;
   const float4* src = reinterpret_cast<const float4*>(X + row * ldx);
   const int64_t n4 = cols >> 2;
@@ -634,17 +645,11 @@ __global__ __launch_bounds__(256) void scatter_mask16_kernel(const uint64_t* __r
   }
 }
 
-// exclusive scans of two count vectors in one launch (block 0: first, block 1: second)
-__global__ __launch_bounds__(1024) void scan_pair_kernel(const int32_t* t0, int64_t n0, int32_t* p0, int64_t* z0,
-                                                         const int32_t* t1, int64_t n1, int32_t* p1, int64_t* z1) {
-  const int32_t* totals = blockIdx.x == 0 ? t0 : t1;
-  const int64_t nvec = blockIdx.x == 0 ? n0 : n1;
-  int32_t* ptr = blockIdx.x == 0 ? p0 : p1;
-  int64_t* nnz_dev = blockIdx.x == 0 ? z0 : z1;
-  if (!totals) return;
+// exclusive scan of one count vector by a block of 1024 threads
+__device__ __forceinline__ void scan_block(const int32_t* totals, int64_t nvec, int32_t* ptr, int64_t* nnz_dev,
+                                           int64_t* wave_sum) {
   // thread t owns the `per` consecutive vectors from t * per on: one block-wide scan of the
   // per-thread sums, whatever the length
-  __shared__ int64_t wave_sum[16];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int64_t per = (nvec + 1023) / 1024;
   const int64_t v0 = tid * per, v1 = v0 + per < nvec ? v0 + per : nvec;
@@ -688,6 +693,43 @@ __global__ __launch_bounds__(1024) void scan_pair_kernel(const int32_t* t0, int6
   }
 }
 
+// Exclusive scans of two count vectors in one launch.  Two blocks, one scan each; or, when the
+// execution of each term is decided on the device (dec.paths != null), ONE block that scans
+// both, then takes that decision from the two totals and writes the call's statistics, so that
+// neither needs a launch of its own.
+__global__ __launch_bounds__(1024) void scan_pair_kernel(const int32_t* t0, int64_t n0, int32_t* p0, int64_t* z0,
+                                                         const int32_t* t1, int64_t n1, int32_t* p1, int64_t* z1,
+                                                         ScanDecision dec) {
+  __shared__ int64_t wave_sum[16];
+  if (!dec.paths) {
+    if (blockIdx.x == 0 ? t0 != nullptr : t1 != nullptr)
+      scan_block(blockIdx.x == 0 ? t0 : t1, blockIdx.x == 0 ? n0 : n1, blockIdx.x == 0 ? p0 : p1,
+                 blockIdx.x == 0 ? z0 : z1, wave_sum);
+    return;
+  }
+  if (t0) scan_block(t0, n0, p0, z0, wave_sum);
+  __syncthreads();                                   // (wave_sum is reused; z0 is visible to the block)
+  if (t1) scan_block(t1, n1, p1, z1, wave_sum);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int64_t na = t0 ? *z0 : 0, nb = t1 ? *z1 : 0;
+    const int pa = t0 ? (na >= dec.min_mfma_a ? 2 : 1) : 0;
+    const int pb = t1 ? (nb >= dec.min_mfma_b ? 2 : 1) : 0;
+    dec.paths[0] = pa;
+    dec.paths[1] = pb;
+    if (dec.seen && pa) dec.seen[0] = pa;
+    if (dec.seen && pb) dec.seen[1] = pb;
+    if (dec.stats) {
+      dec.stats->nnz_a = na;
+      dec.stats->nnz_b = nb;
+      dec.stats->path_a = pa;
+      dec.stats->path_b = pb;
+      dec.stats->overflow = (na > dec.cap_a ? 1 : 0) | (nb > dec.cap_b ? 2 : 0);
+      dec.stats->reserved = 0;
+    }
+  }
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 }  // namespace
@@ -701,13 +743,15 @@ bool rows_fused_ok(const float* X, int64_t cols, int64_t ldx, const int8_t* Q, i
 hipError_t launch_rows_fused(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                              int8_t* Q, int64_t ldq, float* scale, float* lambda, int8_t* Rq, int64_t ldr,
                              float* rscale, float* rlambda, hipStream_t st, const float* given_scale,
-                             const float* given_lambda) {
+                             const float* given_lambda, const ClearList* clear) {
   if (rows <= 0) return hipSuccess;
+  ClearList clr = {nullptr, 0, nullptr, 0, nullptr, 0};
+  if (clear) clr = *clear;                                   // (the caller has checked rows_fused_can_clear)
   dim3 grid((unsigned)rows), block(256);
   const float qm = (float)qmax;
 #define SRQ_ROWS(NV4)                                                                                        \
   hipLaunchKernelGGL(rows_fused_kernel<NV4>, grid, block, 0, st, X, cols, ldx, qm, trunc, Q, ldq, scale,     \
-                     lambda, Rq, ldr, rscale, rlambda, given_scale, given_lambda)
+                     lambda, Rq, ldr, rscale, rlambda, given_scale, given_lambda, clr)
   if (cols <= 1024) SRQ_ROWS(1);
   else if (cols <= 2048) SRQ_ROWS(2);
   else if (cols <= 4096) SRQ_ROWS(4);
@@ -715,6 +759,11 @@ hipError_t launch_rows_fused(const float* X, int64_t rows, int64_t cols, int64_t
   else SRQ_ROWS(16);
 #undef SRQ_ROWS
   return hipGetLastError();
+}
+
+bool rows_fused_can_clear(int64_t rows, const ClearList& c) {
+  const int64_t threads = rows * 256;
+  return rows > 0 && (!c.a || c.na <= threads) && (!c.b || c.nb <= threads) && (!c.c || c.nc <= threads);
 }
 
 bool rows_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* scale,
@@ -895,8 +944,12 @@ hipError_t launch_scatter_mask(const uint64_t* mask, int64_t nvec, int64_t vecle
 }
 
 hipError_t launch_scan_pair(const int32_t* t0, int64_t n0, int32_t* p0, int64_t* z0, const int32_t* t1,
-                            int64_t n1, int32_t* p1, int64_t* z1, hipStream_t st) {
-  hipLaunchKernelGGL(scan_pair_kernel, dim3(2), dim3(1024), 0, st, t0, n0, p0, z0, t1, n1, p1, z1);
+                            int64_t n1, int32_t* p1, int64_t* z1, hipStream_t st, const ScanDecision* decide) {
+  ScanDecision dec;
+  memset(&dec, 0, sizeof(dec));
+  if (decide) dec = *decide;
+  hipLaunchKernelGGL(scan_pair_kernel, dim3(dec.paths ? 1 : 2), dim3(1024), 0, st, t0, n0, p0, z0, t1, n1, p1, z1,
+                     dec);
   return hipGetLastError();
 }
 

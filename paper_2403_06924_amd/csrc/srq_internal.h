@@ -153,10 +153,18 @@ bool rows_fused_ok(const float* X, int64_t cols, int64_t ldx, const int8_t* Q, i
 // (rscale == null: no residual at all; Rq == null with rscale given: residual scales only;
 //  given_scale / given_lambda: use these per-row values instead of deriving them from the row's
 //  maximum, and leave scale / lambda unwritten; rlambda may be null)
+// up to three arrays of 32-bit words that launch_rows_fused zeroes on the side
+struct ClearList {
+  uint32_t* a; int64_t na;
+  uint32_t* b; int64_t nb;
+  uint32_t* c; int64_t nc;
+};
+bool rows_fused_can_clear(int64_t rows, const ClearList& c);   // one word per thread and array
 hipError_t launch_rows_fused(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
                              int8_t* Q, int64_t ldq, float* scale, float* lambda, int8_t* Rq, int64_t ldr,
                              float* rscale, float* rlambda, hipStream_t st, const float* given_scale = nullptr,
-                             const float* given_lambda = nullptr);
+                             const float* given_lambda = nullptr,
+                             const ClearList* clear = nullptr);
 bool rows_resid_em_ok(const float* X, int64_t rows, int64_t cols, int64_t ldx, const float* scale,
                       const float* lambda, const float* rlambda, const int8_t* Rem, int64_t ldem);
 hipError_t launch_rows_resid_em(const float* X, int64_t rows, int64_t cols, int64_t ldx, int qmax, int trunc,
@@ -208,8 +216,19 @@ hipError_t launch_scatter_mask(const uint64_t* mask, int64_t nvec, int64_t vecle
                                const int32_t* ptr, int32_t* idx, int8_t* val, int64_t capacity, int8_t* dense,
                                int64_t ldd, int64_t nnz_hint, hipStream_t st, RunIf dense_if = kAlways);
 // two exclusive scans in one launch; a null totals pointer skips that half
+// decide != null (paths set): one block scans both vectors, then writes SRQ_STRATEGY_AUTO's choice per
+// term (as launch_decide_paths would from the totals z0 / z1: a term whose totals pointer is null
+// does not exist) and, if stats != null, the call's statistics
+struct ScanDecision {
+  int32_t* paths;             // device int32[2]
+  int32_t* seen;              // host-visible int32[2] or null
+  int64_t min_mfma_a, min_mfma_b;
+  srq_stats_t* stats;         // device, or null
+  int64_t cap_a, cap_b;       // capacities the totals are compared with for stats->overflow
+};
 hipError_t launch_scan_pair(const int32_t* t0, int64_t n0, int32_t* p0, int64_t* z0, const int32_t* t1,
-                            int64_t n1, int32_t* p1, int64_t* z1, hipStream_t st);
+                            int64_t n1, int32_t* p1, int64_t* z1, hipStream_t st,
+                            const ScanDecision* decide = nullptr);
 
 // thresholds from the partial sums of the GEMM epilogue
 hipError_t launch_reduce_means(const double* part, int64_t nparts, int64_t nvec, int64_t count,
