@@ -26,8 +26,9 @@ PEAK_VALU_INT_TOPS = 256 * 4 * 16 * 2.4e9 * 2 / 1e12
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # (the chip's clocks settle over the first tens of milliseconds of load: ten warm-up calls)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C3", help="C1..C5 (default C3: 8192^3 with outliers)")
     ap.add_argument("--density", type=float, default=None, help="target density of A' and B'")
     ap.add_argument("--strategy", default="auto", choices=["auto", "valu", "mfma", "smfmac", "colblock"])

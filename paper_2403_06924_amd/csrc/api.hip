@@ -601,8 +601,9 @@ static srq_status_t gemm_i8_impl(srq_handle_t h, int64_t M, int64_t N, int64_t K
   if (drow) {
     // (the persistent kernel leaves one partial per wave, two per 256-wide tile)
     const bool pers = gemm_persistent_ok(M, N, K, Qa, lda, Qb, ldb, ep);
-    SRQ_HIP(h, launch_reduce_means(ep.row_part, pers ? N / 128 : gemm_tiles_n(M, N), M, N, 0.f, drow, nullptr, st));
-    SRQ_HIP(h, launch_reduce_means(ep.col_part, pers ? M / 128 : gemm_tiles_m(M, N), N, M, 0.f, dcol, nullptr, st));
+    SRQ_HIP(h, launch_reduce_means_pair(ep.row_part, pers ? N / 128 : gemm_tiles_n(M, N), M, N, 0.f, drow, nullptr,
+                                        ep.col_part, pers ? M / 128 : gemm_tiles_m(M, N), N, M, 0.f, dcol, nullptr,
+                                        st));
   }
   return SRQ_STATUS_OK;
 }

@@ -15,18 +15,6 @@ __device__ __forceinline__ int quant_code(float x, float lam, float qmax, int tr
 
 // mean_v = (sum over partial sums, fixed order) / count, rounded once to float;
 // thresh_v = fl(theta * mean_v)
-__global__ void reduce_means_kernel(const double* __restrict__ part, int64_t nparts, int64_t nvec,
-                                    double count, float theta, float* __restrict__ mean,
-                                    float* __restrict__ thresh) {
-  int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (v >= nvec) return;
-  double s = 0.0;
-  for (int64_t p = 0; p < nparts; ++p) s += part[p * nvec + v];
-  float m = (float)(s / count);
-  if (mean) mean[v] = m;
-  if (thresh) thresh[v] = theta * m;
-}
-
 // both mean vectors of one product in a single launch: vectors [0, n0) are rows, the rest columns
 __global__ void reduce_means_pair_kernel(const double* __restrict__ part0, int64_t nparts0, int64_t n0,
                                          double count0, float theta0, float* __restrict__ mean0,
@@ -44,7 +32,8 @@ __global__ void reduce_means_pair_kernel(const double* __restrict__ part0, int64
   for (int64_t p = 0; p < nparts; ++p) s += part[p * nvec + v];   // fixed order: reproducible means
   float m = (float)(s / (second ? count1 : count0));
   (second ? mean1 : mean0)[v] = m;
-  (second ? thresh1 : thresh0)[v] = (second ? theta1 : theta0) * m;
+  float* thresh = second ? thresh1 : thresh0;       // (null: the means alone are wanted)
+  if (thresh) thresh[v] = (second ? theta1 : theta0) * m;
 }
 
 // ---- vectors are rows: one wave per (row, chunk of kSelChunk consecutive elements) ----
@@ -223,14 +212,6 @@ __global__ void stats_kernel(const int64_t* nnz_a, const int64_t* nnz_b, int pat
 }
 
 }  // namespace
-
-hipError_t launch_reduce_means(const double* part, int64_t nparts, int64_t nvec, int64_t count,
-                               float theta, float* mean, float* thresh, hipStream_t st) {
-  if (nvec <= 0) return hipSuccess;
-  hipLaunchKernelGGL(reduce_means_kernel, dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, part,
-                     nparts, nvec, (double)count, theta, mean, thresh);
-  return hipGetLastError();
-}
 
 hipError_t launch_reduce_means_pair(const double* part0, int64_t nparts0, int64_t n0, int64_t count0, float theta0,
                                     float* mean0, float* thresh0, const double* part1, int64_t nparts1,

@@ -231,9 +231,6 @@ hipError_t launch_scan_pair(const int32_t* t0, int64_t n0, int32_t* p0, int64_t*
                             const ScanDecision* decide = nullptr);
 
 // thresholds from the partial sums of the GEMM epilogue
-hipError_t launch_reduce_means(const double* part, int64_t nparts, int64_t nvec, int64_t count,
-                               float theta, float* mean, float* thresh, hipStream_t st);
-
 hipError_t launch_reduce_means_pair(const double* part0, int64_t nparts0, int64_t n0, int64_t count0, float theta0,
                                     float* mean0, float* thresh0, const double* part1, int64_t nparts1,
                                     int64_t n1, int64_t count1, float theta1, float* mean1, float* thresh1,
