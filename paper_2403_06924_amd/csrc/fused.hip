@@ -645,72 +645,86 @@ __global__ __launch_bounds__(256) void scatter_mask16_kernel(const uint64_t* __r
   }
 }
 
-// exclusive scan of one count vector by a block of 1024 threads
-__device__ __forceinline__ void scan_block(const int32_t* totals, int64_t nvec, int32_t* ptr, int64_t* nnz_dev,
-                                           int64_t* wave_sum) {
-  // thread t owns the `per` consecutive vectors from t * per on: one block-wide scan of the
-  // per-thread sums, whatever the length
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int64_t per = (nvec + 1023) / 1024;
-  const int64_t v0 = tid * per, v1 = v0 + per < nvec ? v0 + per : nvec;
-  // (spans of up to sixteen vectors are held in registers: their loads are independent and
-  // all in flight at once)
-  constexpr int kHeld = 16;
-  int32_t held[kHeld];
-  int64_t x = 0;
-  if (per <= kHeld) {
+// Exclusive scan of one count vector by a group of NT threads of a block (tid = index in the group,
+// wave_sum = NT / 64 words of LDS of the group's own); the block-wide barrier between the two
+// phases is the caller's, so that two groups can scan two vectors side by side.  totals == null:
+// nothing to do in either phase.
+template <int NT>
+struct ScanGroup {
+  static constexpr int kHeld = 32;                    // spans of up to 32 vectors are held in registers:
+  int32_t held[kHeld];                                // their loads are independent and all in flight at once
+  int64_t x, inc, per, v0, v1;
+  __device__ __forceinline__ void sums(const int32_t* totals, int64_t nvec, int tid, int64_t* wave_sum) {
+    if (!totals) return;
+    // thread t owns the `per` consecutive vectors from t * per on
+    per = (nvec + NT - 1) / NT;
+    v0 = tid * per;
+    v1 = v0 + per < nvec ? v0 + per : nvec;
+    x = 0;
+    if (per <= kHeld) {
 #pragma unroll
-    for (int i = 0; i < kHeld; ++i) held[i] = v0 + i < v1 ? totals[v0 + i] : 0;
+      for (int i = 0; i < kHeld; ++i) held[i] = v0 + i < v1 ? totals[v0 + i] : 0;
 #pragma unroll
-    for (int i = 0; i < kHeld; ++i) x += held[i];
-  } else {
-    for (int64_t v = v0; v < v1; ++v) x += totals[v];
-  }
-  int64_t inc = x;
-  for (int d = 1; d < 64; d <<= 1) {
-    int64_t y = __shfl_up(inc, d, 64);
-    if (lane >= d) inc += y;
-  }
-  if (lane == 63) wave_sum[w] = inc;
-  __syncthreads();
-  int64_t run = inc - x;                              // exclusive prefix of this thread's span
-  for (int i = 0; i < w; ++i) run += wave_sum[i];
-  if (per <= kHeld) {
-#pragma unroll
-    for (int i = 0; i < kHeld; ++i) {
-      if (v0 + i < v1) ptr[v0 + i] = (int32_t)run;
-      run += held[i];
+      for (int i = 0; i < kHeld; ++i) x += held[i];
+    } else {
+      for (int64_t v = v0; v < v1; ++v) x += totals[v];
     }
-  } else {
-    for (int64_t v = v0; v < v1; ++v) {
-      ptr[v] = (int32_t)run;
-      run += totals[v];
+    const int lane = tid & 63;
+    inc = x;
+    for (int d = 1; d < 64; d <<= 1) {
+      int64_t y = __shfl_up(inc, d, 64);
+      if (lane >= d) inc += y;
+    }
+    if (lane == 63) wave_sum[tid >> 6] = inc;
+  }
+  __device__ __forceinline__ void offsets(const int32_t* totals, int64_t nvec, int32_t* ptr, int64_t* nnz_dev,
+                                          int tid, const int64_t* wave_sum) {
+    if (!totals) return;
+    int64_t run = inc - x;                            // exclusive prefix of this thread's span
+    for (int i = 0; i < (tid >> 6); ++i) run += wave_sum[i];
+    if (per <= kHeld) {
+#pragma unroll
+      for (int i = 0; i < kHeld; ++i) {
+        if (v0 + i < v1) ptr[v0 + i] = (int32_t)run;
+        run += held[i];
+      }
+    } else {
+      for (int64_t v = v0; v < v1; ++v) {
+        ptr[v] = (int32_t)run;
+        run += totals[v];
+      }
+    }
+    if (tid == NT - 1) {
+      ptr[nvec] = (int32_t)run;
+      if (nnz_dev) *nnz_dev = run;
     }
   }
-  if (tid == 1023) {
-    ptr[nvec] = (int32_t)run;
-    if (nnz_dev) *nnz_dev = run;
-  }
-}
+};
 
-// Exclusive scans of two count vectors in one launch.  Two blocks, one scan each; or, when the
-// execution of each term is decided on the device (dec.paths != null), ONE block that scans
-// both, then takes that decision from the two totals and writes the call's statistics, so that
-// neither needs a launch of its own.
+// Exclusive scans of two count vectors in one launch.  Two blocks of 1024 threads, one scan each;
+// or, when the execution of each term is decided on the device (dec.paths != null), ONE block
+// whose halves scan one vector each, after which its first thread takes that decision from the
+// two totals and writes the call's statistics, so that neither needs a launch of its own.
 __global__ __launch_bounds__(1024) void scan_pair_kernel(const int32_t* t0, int64_t n0, int32_t* p0, int64_t* z0,
                                                          const int32_t* t1, int64_t n1, int32_t* p1, int64_t* z1,
                                                          ScanDecision dec) {
   __shared__ int64_t wave_sum[16];
   if (!dec.paths) {
-    if (blockIdx.x == 0 ? t0 != nullptr : t1 != nullptr)
-      scan_block(blockIdx.x == 0 ? t0 : t1, blockIdx.x == 0 ? n0 : n1, blockIdx.x == 0 ? p0 : p1,
-                 blockIdx.x == 0 ? z0 : z1, wave_sum);
+    const bool first = blockIdx.x == 0;
+    ScanGroup<1024> g;
+    g.sums(first ? t0 : t1, first ? n0 : n1, threadIdx.x, wave_sum);
+    __syncthreads();
+    g.offsets(first ? t0 : t1, first ? n0 : n1, first ? p0 : p1, first ? z0 : z1, threadIdx.x, wave_sum);
     return;
   }
-  if (t0) scan_block(t0, n0, p0, z0, wave_sum);
-  __syncthreads();                                   // (wave_sum is reused; z0 is visible to the block)
-  if (t1) scan_block(t1, n1, p1, z1, wave_sum);
+  const bool first = threadIdx.x < 512;
+  const int tid = threadIdx.x & 511;
+  int64_t* ws = wave_sum + (first ? 0 : 8);
+  ScanGroup<512> g;
+  g.sums(first ? t0 : t1, first ? n0 : n1, tid, ws);
   __syncthreads();
+  g.offsets(first ? t0 : t1, first ? n0 : n1, first ? p0 : p1, first ? z0 : z1, tid, ws);
+  __syncthreads();                                   // (the totals z0 / z1 are visible to the block)
   if (threadIdx.x == 0) {
     const int64_t na = t0 ? *z0 : 0, nb = t1 ? *z1 : 0;
     const int pa = t0 ? (na >= dec.min_mfma_a ? 2 : 1) : 0;
