@@ -253,6 +253,18 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(int64_t M, int64_t N, int6
         for (int b = 0; b < C::TN; ++b) old[b][v] = (gi < M && colok[b]) ? crow[b * 32] : 0.f;
       }
     }
+    // (the band of Cin as well: one batch of loads, not one round trip per element)
+    const bool has_beta = ep.final_scale && ep.beta != 0.f;
+    float cin[C::TN][16];
+    if (has_beta) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t gi = m0 + rbase + 8 * (v >> 2) + (v & 3);
+        const float* cirow = ep.Cin + gi * ep.ldcin + n0 + cbase;
+#pragma unroll
+        for (int b = 0; b < C::TN; ++b) cin[b][v] = (gi < M && colok[b]) ? cirow[b * 32] : 0.f;
+      }
+    }
     float ad[C::TN][16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -271,7 +283,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(int64_t M, int64_t N, int6
           float out = first ? d : old[b][v] + d;
           if (ep.final_scale) {
             out = ep.alpha * out;
-            if (ep.beta != 0.f) out = out + ep.beta * ep.Cin[gi * ep.ldcin + n0 + cbase + b * 32];
+            if (has_beta) out = out + ep.beta * cin[b][v];
           }
           crow[b * 32] = out;
         } else {

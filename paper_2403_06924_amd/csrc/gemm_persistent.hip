@@ -155,6 +155,25 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
+  // Accumulate mode reads the tile of C it adds to.  Every compute unit reaches its epilogue at
+  // about the same time, so loads issued there arrive as one burst per round while the memory
+  // system idles in between: the first band of the tile (the lane's 16 rows x TN columns of the
+  // first 32 rows of its wave tile) is therefore fetched during the K loop instead, a slice per
+  // K-tile over the kPfTiles K-tiles before the last one, and waits in registers.
+  constexpr int kPfBands = 1;                       // bands fetched ahead (of TM); two cost more in spills than they hide
+  constexpr int kPfTiles = 8 * kPfBands;            // 16 rows x TN values per band = 8 slices of 2 rows
+  const bool pf_on = MODE == kGemmAccum && !SCALE && nk > kPfTiles;   // (alpha / beta need the registers)
+  const int64_t pf0 = nk - 1 - kPfTiles;            // K-tile that issues slice 0
+  float pre[kPfBands][TN][16];
+#pragma unroll
+  for (int a = 0; a < kPfBands; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) pre[a][b][v] = 0.f;
+  const int half = lane >> 5, cl = lane & 31;
+  const int cbase = wn * (BN / 2) + cl;
+
   const int64_t my_tiles = (total - blockIdx.x + G - 1) / G;
   int g = 0;                                        // parity of the K-tile stream across tiles
   int prod = p_lo;                                  // product being multiplied (pairs: 0, 1, 0, 1, ...)
@@ -180,6 +199,23 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
             issue_load(cur, a * TN + b);
             __builtin_amdgcn_sched_barrier(0);
           }
+        if (MODE == kGemmAccum && pf_on && kt >= pf0 && kt < pf0 + kPfTiles) {
+          // slice kt - pf0 of the first band of C: rows 8 (s >> 1) + 2 (s & 1) + {0, 1} of the band
+          const float* cband0 = ep.C + (tile_m * BM + wm * (BM / 2) + 4 * half) * ep.ldc + tile_n * BN + cbase;
+          const bool cached = p_lo != p_hi && prod == 1;
+#pragma unroll
+          for (int sl = 0; sl < kPfTiles; ++sl)
+            if (kt - pf0 == sl) {
+#pragma unroll
+              for (int vv = 0; vv < 2; ++vv)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                  const int a = sl >> 3, v = 2 * (sl & 7) + vv;
+                  const float* src = &cband0[(int64_t)(a * 32 + 8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32];
+                  pre[a][b][v] = cached ? *src : __builtin_nontemporal_load(src);
+                }
+            }
+        }
       } else {
         fread(cur, s + 1, (s + 1) & 1);
 #pragma unroll
@@ -205,8 +241,6 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
     sc_col[tid] = sreg_col;
     __syncthreads();
     const int64_t m0 = tile_m * BM, n0 = tile_n * BN;
-    const int half = lane >> 5, cl = lane & 31;
-    const int cbase = wn * (BN / 2) + cl;
     double colsum[TN];
     float scol[TN];
 #pragma unroll
@@ -217,6 +251,10 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
     // C goes around the caches (it would evict the FP32 operands the next stages stream), except
     // between the two products of a pair: the first leaves its tile cached for the second
     const bool do_scale = SCALE && prod == nprod - 1;
+    // (alpha, beta and the stride of Cin are read here, not kept in registers through the K loop)
+    const float alpha = SCALE ? ep.alpha : 1.f, beta = SCALE ? ep.beta : 0.f;
+    const bool has_beta = SCALE && do_scale && beta != 0.f;
+    const int64_t ldcin = SCALE ? ep.ldcin : 0;
     auto bands = [&](auto cached_load_tag, auto cached_store_tag) {
     constexpr bool CLOAD = decltype(cached_load_tag)::value, CSTORE = decltype(cached_store_tag)::value;
 #pragma unroll
@@ -224,14 +262,30 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
       const int rbase = wm * (BM / 2) + a * 32 + 4 * half;
       float* cband = ep.C + (m0 + rbase) * ep.ldc + n0 + cbase;
       float x[TN][16];
-      if (MODE == kGemmAccum) {
+      float cin[TN][16];                              // the band of Cin, all loads in flight at once
+      if (SCALE && has_beta) {
+        const float* cinband = ep.Cin + (m0 + rbase) * ldcin + n0 + cbase;
 #pragma unroll
         for (int v = 0; v < 16; ++v)
 #pragma unroll
-          for (int b = 0; b < TN; ++b) {
-            const float* src = &cband[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32];
-            x[b][v] = CLOAD ? *src : __builtin_nontemporal_load(src);
-          }
+          for (int b = 0; b < TN; ++b)
+            cin[b][v] = __builtin_nontemporal_load(&cinband[(int64_t)(8 * (v >> 2) + (v & 3)) * ldcin + b * 32]);
+      }
+      if (MODE == kGemmAccum) {
+        if (a < kPfBands && pf_on) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) x[b][v] = pre[a < kPfBands ? a : 0][b][v];
+        } else {
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+              const float* src = &cband[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32];
+              x[b][v] = CLOAD ? *src : __builtin_nontemporal_load(src);
+            }
+        }
       }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -242,8 +296,8 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
           const float d = (float)acc[a][b][v] * (srow * scol[b]);
           float out = MODE == kGemmFirst ? d : x[b][v] + d;
           if (SCALE && do_scale) {
-            out = ep.alpha * out;
-            if (ep.beta != 0.f) out = out + ep.beta * ep.Cin[(m0 + rbase + ro) * ep.ldcin + n0 + cbase + b * 32];
+            out = alpha * out;
+            if (has_beta) out = out + beta * cin[b][v];
           }
           if (CSTORE) cband[(int64_t)ro * ep.ldc + b * 32] = out;
           else __builtin_nontemporal_store(out, &cband[(int64_t)ro * ep.ldc + b * 32]);

@@ -205,6 +205,9 @@ __global__ __launch_bounds__(256) void gemm_i8_small_kernel(int64_t M, int64_t N
       scol[b] = sc_col[cbase + b * 32];
     }
     const bool do_scale = SCALE && prod == nprod - 1;
+    const float alpha = SCALE ? ep.alpha : 1.f, beta = SCALE ? ep.beta : 0.f;
+    const bool has_beta = SCALE && do_scale && beta != 0.f;
+    const int64_t ldcin = SCALE ? ep.ldcin : 0;
     // C goes around the caches, except between the two products of a pair
     auto bands = [&](auto cached_load_tag, auto cached_store_tag) {
       constexpr bool CLOAD = decltype(cached_load_tag)::value, CSTORE = decltype(cached_store_tag)::value;
@@ -213,6 +216,15 @@ __global__ __launch_bounds__(256) void gemm_i8_small_kernel(int64_t M, int64_t N
         const int rbase = wm * (BM / 2) + a * 32 + 4 * half;
         float* cband = ep.C + (m0 + rbase) * ep.ldc + n0 + cbase;
         float x[TN][16];
+        float cin[TN][16];                            // the band of Cin, all loads in flight at once
+        if (SCALE && has_beta) {
+          const float* cinband = ep.Cin + (m0 + rbase) * ldcin + n0 + cbase;
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+              cin[b][v] = __builtin_nontemporal_load(&cinband[(int64_t)(8 * (v >> 2) + (v & 3)) * ldcin + b * 32]);
+        }
         if (MODE == kGemmAccum) {
 #pragma unroll
           for (int v = 0; v < 16; ++v)
@@ -231,8 +243,8 @@ __global__ __launch_bounds__(256) void gemm_i8_small_kernel(int64_t M, int64_t N
             const float d = (float)acc[a][b][v] * (srow * scol[b]);
             float out = MODE == kGemmFirst ? d : x[b][v] + d;
             if (SCALE && do_scale) {
-              out = ep.alpha * out;
-              if (ep.beta != 0.f) out = out + ep.beta * ep.Cin[(m0 + rbase + ro) * ep.ldcin + n0 + cbase + b * 32];
+              out = alpha * out;
+              if (has_beta) out = out + beta * cin[b][v];
             }
             if (CSTORE) cband[(int64_t)ro * ep.ldc + b * 32] = out;
             else __builtin_nontemporal_store(out, &cband[(int64_t)ro * ep.ldc + b * 32]);

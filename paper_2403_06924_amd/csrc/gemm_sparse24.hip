@@ -379,6 +379,16 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_sparse24_kernel(int64_t K, S
             const float* src = &cband[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32];
             x[b][v] = CLOAD ? *src : __builtin_nontemporal_load(src);
           }
+        const bool has_beta = SCALE && do_scale && ep.beta != 0.f;
+        float cin[TN][16];                            // the band of Cin, all loads in flight at once
+        if (has_beta) {
+          const float* cinband = ep.Cin + (m0 + rbase) * ep.ldcin + n0 + cbase;
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+              cin[b][v] = __builtin_nontemporal_load(&cinband[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldcin + b * 32]);
+        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int ro = 8 * (v >> 2) + (v & 3);
@@ -388,7 +398,7 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_sparse24_kernel(int64_t K, S
             float out = x[b][v] + (float)acc[a][b][v] * (sm * scn[b]);
             if (SCALE && do_scale) {
               out = ep.alpha * out;
-              if (ep.beta != 0.f) out = out + ep.beta * ep.Cin[(m0 + rbase + ro) * ep.ldcin + n0 + cbase + b * 32];
+              if (has_beta) out = out + ep.beta * cin[b][v];
             }
             if (CSTORE) cband[(int64_t)ro * ep.ldc + b * 32] = out;
             else __builtin_nontemporal_store(out, &cband[(int64_t)ro * ep.ldc + b * 32]);
