@@ -727,10 +727,10 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     ++h->prof_calls;
   }
   // the one-pass kernels derive each vector's scale from the data they hold; a matrix-wide
-  // scale needs all maxima first and takes the staged kernels
+  // scale needs all maxima first: one more pass, then the same kernels with the scales given
   const bool global_scale = h->scale_mode == SRQ_SCALE_GLOBAL;
-  const bool fastA = K > 0 && !global_scale && rows_fused_ok(A, K, lda, p.A_int, Kc, p.RA_int, Kc);
-  const bool fastB = K > 0 && !global_scale && cols_pass_ok(B, N, ldb);
+  const bool fastA = K > 0 && rows_fused_ok(A, K, lda, p.A_int, Kc, p.RA_int, Kc);
+  const bool fastB = K > 0 && cols_pass_ok(B, N, ldb);
   bool ra_vm_done = false, ra_em_done = false, rb_vm_done = false, rb_em_done = false;
   bool rb_in_select = false, rb_want_em = false, rb_want_vm = false;   // residual codes of B left to the selection pass
   // lines 1: Quant.  amax per vector -> scale, lambda -> codes (and max |residual| per vector)
@@ -768,9 +768,18 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // costs the pass that writes the other layout once the decision is known)
     // (this launch also zeroes what B's passes accumulate into, see below)
     b_cleared = fastB && rows_fused_can_clear(M, b_clear);
+    if (global_scale) {
+      // one scale for the whole matrix: the maximum first (one more read of A), then the one-pass
+      // kernel with the scales given; the residual codes keep a scale per row
+      SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_a), M, 0, st));
+      SRQ_HIP(h, launch_amax(A, M, K, lda, SRQ_AXIS_ROW, reinterpret_cast<uint32_t*>(p.s_a), st));
+      SRQ_HIP(h, launch_broadcast_max(reinterpret_cast<uint32_t*>(p.s_a), M, st));
+      SRQ_HIP(h, launch_scales(reinterpret_cast<uint32_t*>(p.s_a), p.lam_a, M, qmax, st));
+    }
     SRQ_HIP(h, launch_rows_fused(A, M, K, lda, qmax, trunc, p.A_int, Kc, p.s_a, p.lam_a,
                                  (comp && !skip_ra_vm) ? p.RA_int : nullptr, Kc, comp ? p.s_ra : nullptr,
-                                 comp ? p.lam_ra : nullptr, st, nullptr, nullptr, b_cleared ? &b_clear : nullptr));
+                                 comp ? p.lam_ra : nullptr, st, global_scale ? p.s_a : nullptr,
+                                 global_scale ? p.lam_a : nullptr, b_cleared ? &b_clear : nullptr));
     ra_vm_done = comp && !skip_ra_vm;
   } else {
     SRQ_HIP(h, launch_fill_u32(reinterpret_cast<uint32_t*>(p.s_a), M, 0, st));
@@ -789,6 +798,8 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // passes derive the scales from the maxima themselves
     if (!b_cleared) SRQ_HIP(h, launch_fill3_u32(b_clear.a, b_clear.na, b_clear.b, b_clear.nb, b_clear.c, b_clear.nc, st));
     SRQ_HIP(h, launch_cols_amax(B, K, N, ldb, p.amax_b, st));
+    // (one scale for the whole matrix: every column takes the largest of the maxima)
+    if (global_scale) SRQ_HIP(h, launch_broadcast_max(p.amax_b, N, st));
     SRQ_HIP(h, launch_cols_codes_from_amax(B, K, N, ldb, qmax, trunc, p.amax_b, p.s_b, p.lam_b, p.B_int, Kc,
                                            comp ? p.ramax_b : nullptr, st));
     if (comp) {
