@@ -231,7 +231,8 @@ srq_status_t srq_build_sparse_residual(srq_handle_t handle, const float* X, int6
  * in double in a fixed order; both may be NULL.
  * Any shape and alignment is accepted; the fast kernels need 16-byte aligned Qa, Qb, lda and ldb
  * multiples of 16 and K a multiple of 64 (pad K with zero codes to get there: they add nothing),
- * the persistent one in addition M and N multiples of 256 with at least 256 tiles, and the
+ * the persistent one in addition at least 256 whole tiles of 256 x 256 and K a multiple of 128 (it
+ * then takes the block of whole tiles and the plain kernel the strips beside it), and the
  * pipelined small-tile one (problems below that) M, N and K multiples of 128. */
 srq_status_t srq_gemm_i8(srq_handle_t handle, int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
                          const float* sa, const int8_t* Qb, int64_t ldb, const float* sb, float* D_F,

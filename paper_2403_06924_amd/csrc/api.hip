@@ -600,10 +600,10 @@ static srq_status_t gemm_i8_impl(srq_handle_t h, int64_t M, int64_t N, int64_t K
   SRQ_HIP(h, launch_gemm_i8(M, N, K, Qa, lda, Qb, ldb, ep, st));
   if (drow) {
     // (the persistent kernel leaves one partial per wave, two per 256-wide tile)
-    const bool pers = gemm_persistent_ok(M, N, K, Qa, lda, Qb, ldb, ep);
-    SRQ_HIP(h, launch_reduce_means_pair(ep.row_part, pers ? N / 128 : gemm_tiles_n(M, N), M, N, 0.f, drow, nullptr,
-                                        ep.col_part, pers ? M / 128 : gemm_tiles_m(M, N), N, M, 0.f, dcol, nullptr,
-                                        st));
+    int64_t parts_n, parts_m;
+    gemm_sum_parts(M, N, K, Qa, lda, Qb, ldb, ep, &parts_n, &parts_m);
+    SRQ_HIP(h, launch_reduce_means_pair(ep.row_part, parts_n, M, N, 0.f, drow, nullptr, ep.col_part, parts_m, N, M, 0.f,
+                                        dcol, nullptr, st));
   }
   return SRQ_STATUS_OK;
 }
@@ -874,10 +874,10 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     StageTimer tm(h, st, SRQ_STAGE_SELECT);
     // line 7: GetAvgVec, and the thresholds of Eq. avgQuan
     // (the persistent kernel leaves one partial per wave, two per 256-wide tile)
-    const bool pers = gemm_persistent_ok(M, N, Kc, p.A_int, Kc, p.B_int, Kc, ep);
-    SRQ_HIP(h, launch_reduce_means_pair(p.row_part, pers ? N / 128 : gemm_tiles_n(M, N), M, N, theta_a, p.drow, p.t_a,
-                                        p.col_part, pers ? M / 128 : gemm_tiles_m(M, N), N, M, theta_b, p.dcol,
-                                        p.t_b, st));
+    int64_t parts_n, parts_m;
+    gemm_sum_parts(M, N, Kc, p.A_int, Kc, p.B_int, Kc, ep, &parts_n, &parts_m);
+    SRQ_HIP(h, launch_reduce_means_pair(p.row_part, parts_n, M, N, theta_a, p.drow, p.t_a, p.col_part, parts_m, N, M,
+                                        theta_b, p.dcol, p.t_b, st));
     im.drow = p.drow; im.dcol = p.dcol; im.t_a = p.t_a; im.t_b = p.t_b;
     // lines 8-10: Reduce.  Keep-bits and per-vector counts, then the prefix scans
     int64_t chk = select_chunks(K);

@@ -328,7 +328,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(int64_t M, int64_t N, int6
   if (sums) {
     __syncthreads();
     for (int t = tid; t < BM; t += 256)
-      if (m0 + t < M) ep.row_part[tile_n * M + m0 + t] = red[t] + red[RED + t];
+      if (m0 + t < M) ep.row_part[tile_n * (ep.part_ld_m ? ep.part_ld_m : M) + m0 + t] = red[t] + red[RED + t];
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < C::TN; ++b) {
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(int64_t M, int64_t N, int6
     }
     __syncthreads();
     for (int t = tid; t < BN; t += 256)
-      if (n0 + t < N) ep.col_part[tile_m * N + n0 + t] = red[t] + red[RED + t];
+      if (n0 + t < N) ep.col_part[tile_m * (ep.part_ld_n ? ep.part_ld_n : N) + n0 + t] = red[t] + red[RED + t];
   }
 }
 
@@ -387,6 +387,28 @@ int gemm_tile_n() { return 128; }
 int64_t gemm_tiles_m(int64_t M, int64_t N) { int t = use_big_tiles(M, N) ? 256 : 128; return (M + t - 1) / t; }
 int64_t gemm_tiles_n(int64_t M, int64_t N) { int t = use_big_tiles(M, N) ? 256 : 128; return (N + t - 1) / t; }
 
+// A large problem whose M or N is not a multiple of 256: the largest block of whole 256 x 256
+// tiles [0, M0) x [0, N0) can still take the persistent kernel, and the plain kernel (128 x 128
+// tiles) then only multiplies the strip of columns [N0, N) and the strip of rows [M0, M).
+static bool split_ok(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb, int64_t ldb,
+                     const GemmEpilogue& ep, int64_t* M0, int64_t* N0) {
+  *M0 = M / 256 * 256;
+  *N0 = N / 256 * 256;
+  if (*M0 <= 0 || *N0 <= 0 || (*M0 == M && *N0 == N)) return false;
+  return gemm_persistent_ok(*M0, *N0, K, Qa, lda, Qb, ldb, ep);
+}
+
+void gemm_sum_parts(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb, int64_t ldb,
+                    const GemmEpilogue& ep, int64_t* parts_n, int64_t* parts_m) {
+  int64_t M0, N0;
+  // (the persistent and the small-tile kernel leave one partial per 128 columns resp. rows; so does
+  // the split, whose strips run with 128 x 128 tiles)
+  const bool per128 = gemm_persistent_ok(M, N, K, Qa, lda, Qb, ldb, ep) ||
+                      gemm_small_ok(M, N, K, Qa, lda, Qb, ldb, ep) || split_ok(M, N, K, Qa, lda, Qb, ldb, ep, &M0, &N0);
+  *parts_n = per128 ? (N + 127) / 128 : gemm_tiles_n(M, N);
+  *parts_m = per128 ? (M + 127) / 128 : gemm_tiles_m(M, N);
+}
+
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,
                           const int8_t* Qb, int64_t ldb, const GemmEpilogue& ep, hipStream_t st) {
   if (M <= 0 || N <= 0) return hipSuccess;
@@ -396,6 +418,34 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int
   // fast path: every 16-byte piece is aligned and inside [0,K)
   bool fast = ((reinterpret_cast<uintptr_t>(Qa) | reinterpret_cast<uintptr_t>(Qb)) & 15) == 0 &&
               (lda % 16) == 0 && (ldb % 16) == 0 && K > 0 && (K % 64) == 0;
+  int64_t M0, N0;
+  if (split_ok(M, N, K, Qa, lda, Qb, ldb, ep, &M0, &N0)) {
+    GemmEpilogue e = ep;                            // partial sums keep the strides of the whole product
+    e.part_ld_m = ep.part_ld_m ? ep.part_ld_m : M;
+    e.part_ld_n = ep.part_ld_n ? ep.part_ld_n : N;
+    hipError_t err = launch_gemm_i8_persistent(M0, N0, K, Qa, lda, Qb, ldb, e, st);
+    if (err != hipSuccess) return err;
+    if (N0 < N) {                                   // columns [N0, N), every row
+      GemmEpilogue r = e;
+      r.s_col = ep.s_col + N0;
+      r.C = ep.C + N0;
+      if (ep.Cin) r.Cin = ep.Cin + N0;
+      if (ep.row_part) r.row_part = ep.row_part + (N0 / 128) * e.part_ld_m;
+      if (ep.col_part) r.col_part = ep.col_part + N0;
+      err = launch_cfg<128, 128, 64>(M, N - N0, K, Qa, lda, Qb + N0 * ldb, ldb, r, fast, st);
+      if (err != hipSuccess) return err;
+    }
+    if (M0 < M) {                                   // rows [M0, M) of the columns [0, N0)
+      GemmEpilogue b = e;
+      b.s_row = ep.s_row + M0;
+      b.C = ep.C + M0 * ep.ldc;
+      if (ep.Cin) b.Cin = ep.Cin + M0 * ep.ldcin;
+      if (ep.row_part) b.row_part = ep.row_part + M0;
+      if (ep.col_part) b.col_part = ep.col_part + (M0 / 128) * e.part_ld_n;
+      err = launch_cfg<128, 128, 64>(M - M0, N0, K, Qa + M0 * lda, lda, Qb, ldb, b, fast, st);
+    }
+    return err;
+  }
   if (use_big_tiles(M, N)) {
     if (fast && K % 128 == 0) return launch_cfg<256, 256, 128>(M, N, K, Qa, lda, Qb, ldb, ep, fast, st);
     return launch_cfg<256, 256, 64>(M, N, K, Qa, lda, Qb, ldb, ep, fast, st);

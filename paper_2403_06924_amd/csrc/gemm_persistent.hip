@@ -324,7 +324,8 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
         const int v = cl >> 1;
         // each wave leaves its own partial (its 128 columns of the tile): no exchange through LDS
         // and no barrier, so a wave that is done starts on the next tile
-        if (!(cl & 1)) ep.row_part[(2 * tile_n + wn) * M + m0 + rbase + 8 * (v >> 2) + (v & 3)] = (double)r[0];
+        if (!(cl & 1)) ep.row_part[(2 * tile_n + wn) * (ep.part_ld_m ? ep.part_ld_m : M) + m0 + rbase + 8 * (v >> 2) + (v & 3)] =
+              (double)r[0];
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
           float t8[8], t4[4];
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
       for (int b = 0; b < TN; ++b) {
         double c = colsum[b];
         c += __shfl_xor(c, 32, 64);
-        if (half == 0) ep.col_part[(2 * tile_m + wm) * N + n0 + cbase + b * 32] = c;
+        if (half == 0) ep.col_part[(2 * tile_m + wm) * (ep.part_ld_n ? ep.part_ld_n : N) + n0 + cbase + b * 32] = c;
       }
     }
     // next product of this tile, or the next output tile of this workgroup

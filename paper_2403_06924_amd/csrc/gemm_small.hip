@@ -295,8 +295,10 @@ __global__ __launch_bounds__(256) void gemm_i8_small_kernel(int64_t M, int64_t N
         if (half == 0) xcol[wm * BN + cbase + b * 32] = c;
       }
       __syncthreads();
-      if (tid < BM) ep.row_part[tile_n * M + m0 + tid] = (double)xrow[tid] + (double)xrow[BM + tid];
-      else ep.col_part[tile_m * N + n0 + tid - BM] = xcol[tid - BM] + xcol[BN + tid - BM];
+      if (tid < BM)
+        ep.row_part[tile_n * (ep.part_ld_m ? ep.part_ld_m : M) + m0 + tid] = (double)xrow[tid] + (double)xrow[BM + tid];
+      else
+        ep.col_part[tile_m * (ep.part_ld_n ? ep.part_ld_n : N) + n0 + tid - BM] = xcol[tid - BM] + xcol[BN + tid - BM];
     }
     if (prod < p_hi) sreg = tid < BM ? sec.s_row[m0 + tid] : sec.s_col[n0 + tid - BM];
   }

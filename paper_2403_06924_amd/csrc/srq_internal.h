@@ -74,6 +74,9 @@ struct GemmEpilogue {
   // term 1 / term 2; the kernel runs only if both are among those it was launched for
   const int32_t* paths;       // device int32[2] (null: unconditional)
   uint32_t ok_a, ok_b;        // bit p set: path p of term 1 resp. term 2 is acceptable
+  // strides of the partial sums (row_part[part * part_ld_m + row], col_part[part * part_ld_n + col]);
+  // 0: the M resp. N of the launch.  Set when a launch covers a block of a larger product.
+  int64_t part_ld_m, part_ld_n;
   // paired launches only: the two products are decided one by one (product t runs iff the path of
   // term t+1 is acceptable) instead of both or none; alpha / beta go with the second product only
   int each_product;
@@ -239,6 +242,10 @@ hipError_t launch_reduce_means_pair(const double* part0, int64_t nparts0, int64_
 // INT8 GEMM, both operands K-contiguous
 int gemm_tile_m();                          // smallest tile extents (upper bound on tile counts)
 int gemm_tile_n();
+// number of partial sums launch_gemm_i8 leaves per row (parts_n) and per column (parts_m) of D_F
+// for this problem: what the reduction after it has to add up
+void gemm_sum_parts(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda, const int8_t* Qb, int64_t ldb,
+                    const GemmEpilogue& ep, int64_t* parts_n, int64_t* parts_m);
 int64_t gemm_tiles_m(int64_t M, int64_t N);  // tile counts of the configuration launch_gemm_i8 picks
 int64_t gemm_tiles_n(int64_t M, int64_t N);
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t* Qa, int64_t lda,

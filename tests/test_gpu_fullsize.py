@@ -199,10 +199,14 @@ def test_c5_wide_range_sampled(srq, b, density):
     sampled_check(srq, b, "C5", density, 48, seed=13)
 
 
-@pytest.mark.parametrize("shape", [(5888, 5888, 384), (2560, 13312, 640), (4096, 4096, 256), (4352, 4096, 128)])
+@pytest.mark.parametrize("shape", [(5888, 5888, 384), (2560, 13312, 640), (4096, 4096, 256), (4352, 4096, 128),
+                                   (4224, 4096, 256), (4096, 4200, 128), (4300, 4500, 128)])
 def test_persistent_gemm_uneven_tile_counts(srq, b, shape):
     """529 and 520 tiles of 256 x 256 on 256 compute units: workgroups of the persistent kernel
     get different numbers of tiles, and the load cursor runs ahead across tile boundaries.
+    The last three shapes are no multiples of 256: the persistent kernel takes the block of whole
+    tiles, the plain kernel the strips of rows and columns beside it, and the partial sums of
+    |D_F| of the three launches interleave.
     First mode (with the means) and accumulate mode (through the expanded sparse operand),
     element by element."""
     M, N, K = shape
@@ -230,7 +234,7 @@ def test_persistent_gemm_uneven_tile_counts(srq, b, shape):
     assert (host(Cd) == ref_C).all()
 
 
-@pytest.mark.parametrize("shape", [(4352, 4096, 200), (4096, 5120, 129)])
+@pytest.mark.parametrize("shape", [(4352, 4096, 200), (4096, 5120, 129), (4224, 4200, 129)])
 @pytest.mark.parametrize("variant", ["mfma", "auto_sparse", "dense_branch"])
 def test_padded_inner_dimension_through_persistent_kernels(srq, b, shape, variant):
     """K that is no multiple of 64 with M, N multiples of 256: the code matrices are padded to a
