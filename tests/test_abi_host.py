@@ -193,3 +193,22 @@ def test_missing_library_fails_loudly(monkeypatch, lib):
     monkeypatch.setattr(b, "LIB_PATH", os.path.join(ROOT, "does_not_exist", "libsrq.so"))
     with pytest.raises(RuntimeError, match="not built"):
         b.load()
+
+
+def test_handle_settings_validation(dry):
+    """Host-side setters: argument checks without a device (nothing is launched by any of them)."""
+    lib, h = dry.lib, dry.h
+    assert lib.srq_set_auto_hint(h, 0, 0) == b.OK
+    assert lib.srq_set_auto_hint(h, 1, 2) == b.OK
+    assert lib.srq_set_auto_hint(h, 3, 0) == b.INVALID_ARG        # only 0 (none), 1 (vector ALUs), 2 (matrix cores)
+    assert lib.srq_set_auto_hint(h, 0, -1) == b.INVALID_ARG
+    assert lib.srq_set_auto_hint(None, 0, 0) == b.INVALID_ARG
+    assert lib.srq_set_scale_mode(h, b.SCALE_GLOBAL) == b.OK
+    assert lib.srq_set_scale_mode(h, 7) == b.INVALID_ARG
+    assert lib.srq_set_scale_mode(h, b.SCALE_VECTOR) == b.OK
+    ms = (C.c_float * len(b.STAGES))(*([1.0] * len(b.STAGES)))
+    assert lib.srq_profile_read(h, ms) == b.OK and all(x == 0.0 for x in ms)   # nothing recorded: zeros
+    assert lib.srq_profile_read(h, None) == b.INVALID_ARG
+    assert lib.srq_profile_enable(h, 1) == b.NO_DEVICE            # events need a device
+    assert lib.srq_profile_enable(h, 0) == b.OK
+
