@@ -37,9 +37,13 @@ def parse():
     ap.add_argument("--no-accuracy", action="store_true")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the timing of the plain (theta=inf) and unreduced (theta=0) variants")
-    ap.add_argument("--stage", default=None, choices=["quantize", "build_sparse_residual"],
+    ap.add_argument("--stage", default=None, choices=["quantize", "build_sparse_residual", "gemm"],
                     help="time one staged entry point on the workload's operands instead of the whole path "
-                         "(prints its own JSON line: achieved GB/s against the HBM peak)")
+                         "(prints its own JSON line: achieved GB/s against the HBM peak; gemm: srq_gemm_i8 without "
+                         "the means, TOP/s against the INT8 matrix-core peak)")
+    ap.add_argument("--operands", default="workload", choices=["workload", "random", "zeros"],
+                    help="--stage gemm only: the workload's own codes, uniformly random codes or all-zero codes "
+                         "(the chip's clock under load depends on how much the operands toggle)")
     ap.add_argument("--eager", "--no-graph", dest="eager", action="store_true",
                     help="skip the graph replay that is otherwise measured after the timed region and reported "
                          "beside it as `graph_replay`")
@@ -102,6 +106,32 @@ def stage_bench(args, b, torch, h, w, Ad, Bd, sa, sb, drow, dcol, theta_a, theta
     t_a = (drow * theta_a).contiguous()
     t_b = (dcol * theta_b).contiguous()
     nnz = [0, 0]
+    if args.stage == "gemm":
+        if args.operands == "random":
+            Qa = torch.randint(-127, 128, (M, K), dtype=torch.int8, device="cuda")
+            Qb = torch.randint(-127, 128, (N, K), dtype=torch.int8, device="cuda")
+        elif args.operands == "zeros":
+            Qa.zero_()
+            Qb.zero_()
+        out = (torch.empty((M, N), dtype=torch.float32, device="cuda"), None, None)
+        for _ in range(args.warmup):
+            h.gemm_i8(Qa, sa, Qb, sb, want_means=False, out=out)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            h.gemm_i8(Qa, sa, Qb, sb, want_means=False, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        tops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+        print(json.dumps({"metric": "TOP/s of srq_gemm_i8 (first product, no means), %s codes" % args.operands,
+                          "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": ms, "higher_is_better": True, "dtype": "int8", "data": "synthetic",
+                          "config": {"workload": "%s: M=%d N=%d K=%d" % (w.name, M, N, K), "operands": args.operands},
+                          "roofline": {"bound": "mfma", "achieved": tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                                       "frac": tops / PEAK_INT8_TOPS}}))
+        return
 
     def run():
         if args.stage == "quantize":
