@@ -715,6 +715,15 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
   const int trunc = round == SRQ_ROUND_TRUNC;
   const bool scale_needed = alpha != 1.f || beta != 0.f;
   const int64_t Kc = code_ld(K);                 // leading dimension of the K-contiguous code matrices
+  if (strategy == SRQ_STRATEGY_AUTO) {
+    // Problems that the small-tile matrix-core kernel takes: both correction products cost so little
+    // there (one launch of 36 us at 2048^3) that the vector ALUs never win, whatever the density
+    // (measured down to 0.1 %: 0.157 against 0.179 ms per call), so nothing is left to decide.
+    GemmEpilogue probe;
+    memset(&probe, 0, sizeof(probe));
+    probe.mode = kGemmAccum;
+    if (gemm_small_ok(M, N, Kc, p.A_int, Kc, p.B_int, Kc, probe)) strategy = SRQ_STRATEGY_CSR_MFMA;
+  }
 
   srq_intermediates_t& im = h->last;
   memset(&im, 0, sizeof(im));

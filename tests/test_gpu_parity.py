@@ -521,14 +521,28 @@ def test_overflow_in_non_synchronising_modes(srq, b, strategy, shape):
     assert o.error_rel(ref.C, host(C)) <= REL_TOL
 
 
-@pytest.mark.parametrize("shape", [(256, 384, 512), (2304, 2048, 256), (130, 257, 129)])
+def test_auto_on_small_aligned_problems_is_the_matrix_core_execution(srq, b):
+    """Where the small-tile kernel runs the products (M, N multiples of 128 below 256 big tiles) the
+    matrix cores win at any density: SRQ_STRATEGY_AUTO takes them without deciding anything."""
+    A, B = wl.make_inputs("C2", 256, 384, 512)
+    plain = o.quantized_product(A, B)
+    drow, dcol = o.abs_means(plain.D_F)
+    for density in (0.003, 0.05):
+        ta = wl.theta_for_density(A, drow, "row", density)
+        tb = wl.theta_for_density(B, dcol, "col", density)
+        _, _, st = check_against_oracle(srq, b, A, B, ta, tb, strategy=0)
+        assert (st["path_a"], st["path_b"]) == (2, 2)
+
+
+@pytest.mark.parametrize("shape", [(4096, 4096, 128), (2368, 2048, 256), (130, 257, 129)])
 @pytest.mark.parametrize("da,db,want", [(0.003, 0.05, (1, 2)), (0.05, 0.003, (2, 1)), (0.003, 0.003, (1, 1)),
                                         (0.05, 0.05, (2, 2))])
 def test_auto_decides_on_the_device(srq, b, shape, da, db, want):
     """SRQ_STRATEGY_AUTO without the density switch never reads anything back: the executions are
     chosen by a kernel from the counts, per term, and every stage matches the oracle whichever
-    combination comes out and whatever the caller's hint said (right, wrong or none).  The larger
-    shape takes the persistent kernels (paired launch when both terms go to the matrix cores)."""
+    combination comes out and whatever the caller's hint said (right, wrong or none).  The largest
+    shape takes the persistent kernels (one paired launch for whichever terms go to the matrix
+    cores), the others the plain kernel."""
     M, N, K = shape
     A, B = wl.make_inputs("C2", M, N, K)
     plain = o.quantized_product(A, B)
