@@ -579,8 +579,11 @@ def test_stage_timers_sum_over_calls(srq, b):
         for _ in range(3):                                                  # (the first calls are cold)
             srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
         srq.profile_read()
-        srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
-        one = srq.profile_read()
+        singles = []
+        for _ in range(3):
+            srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
+            singles.append(srq.profile_read())
+        one = {k: min(s[k] for s in singles) for k in singles[0]}          # (a single call can be an outlier)
         assert one["quantize"] > 0 and one["gemm"] > 0 and one["select"] > 0 and one["term1"] > 0
         for _ in range(5):
             srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
