@@ -173,7 +173,8 @@ def main():
     args = parse()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build measures one GPU only (the path is a single-device "
-                         "kernel pipeline; see DESIGN.md for how it would shard); run with --gpus 1\n")
+                         "kernel pipeline; sharding would split C by row blocks, one handle per GPU); "
+                         "run with --gpus 1\n")
         sys.exit(2)
     import numpy as np
     import torch
