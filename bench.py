@@ -44,6 +44,10 @@ def parse():
     ap.add_argument("--operands", default="workload", choices=["workload", "random", "zeros"],
                     help="--stage gemm only: the workload's own codes, uniformly random codes or all-zero codes "
                          "(the chip's clock under load depends on how much the operands toggle)")
+    ap.add_argument("--compare-library", action="store_true",
+                    help="--stage gemm only: also time the vendor library's INT8 GEMM (torch._int_mm, INT32 out, no "
+                         "scaling) on the same codes, in alternating blocks of launches, and report it beside "
+                         "the kernel's own figure as `library_int_mm` (a reference point, not part of the path)")
     ap.add_argument("--eager", "--no-graph", dest="eager", action="store_true",
                     help="skip the graph replay that is otherwise measured after the timed region and reported "
                          "beside it as `graph_replay`")
@@ -125,12 +129,35 @@ def stage_bench(args, b, torch, h, w, Ad, Bd, sa, sb, drow, dcol, theta_a, theta
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / args.steps
         tops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
-        print(json.dumps({"metric": "TOP/s of srq_gemm_i8 (first product, no means), %s codes" % args.operands,
-                          "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-                          "ms_per_step": ms, "higher_is_better": True, "dtype": "int8", "data": "synthetic",
-                          "config": {"workload": "%s: M=%d N=%d K=%d" % (w.name, M, N, K), "operands": args.operands},
-                          "roofline": {"bound": "mfma", "achieved": tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                                       "frac": tops / PEAK_INT8_TOPS}}))
+        line = {"metric": "TOP/s of srq_gemm_i8 (first product, no means), %s codes" % args.operands,
+                "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                "ms_per_step": ms, "higher_is_better": True, "dtype": "int8", "data": "synthetic",
+                "config": {"workload": "%s: M=%d N=%d K=%d" % (w.name, M, N, K), "operands": args.operands},
+                "roofline": {"bound": "mfma", "achieved": tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                             "frac": tops / PEAK_INT8_TOPS}}
+        if args.compare_library:
+            # the clock under sustained matrix-core load settles over tens of launches and differs from
+            # box to box, so the two are timed in alternating blocks inside one warm sequence
+            Ci = torch.empty((M, N), dtype=torch.int32, device="cuda")
+            QbT = Qb.t()                              # the library takes B as K x N; this view is column-major
+            blocks, per = 6, max(1, args.steps // 6)
+            t_own, t_lib = [], []
+            for blk in range(blocks + 1):
+                for fn, acc in ((lambda: h.gemm_i8(Qa, sa, Qb, sb, want_means=False, out=out), t_own),
+                                (lambda: torch._int_mm(Qa, QbT, out=Ci), t_lib)):
+                    e0.record()
+                    for _ in range(per):
+                        fn()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    if blk:                           # the first pair of blocks warms both up
+                        acc.append(e0.elapsed_time(e1) / per)
+            mo, ml = sum(t_own) / len(t_own), sum(t_lib) / len(t_lib)
+            line["library_int_mm"] = {"ms_per_launch": ml, "value": 2.0 * M * N * K / (ml * 1e-3) / 1e12, "unit": "TOPS",
+                                      "own_ms_per_launch_alternating": mo, "own_over_library_time": mo / ml,
+                                      "note": "torch._int_mm (INT32 output, no scales) on the same codes; blocks of %d "
+                                              "launches, alternating, %d blocks each" % (per, blocks)}
+        print(json.dumps(line))
         return
 
     def run():

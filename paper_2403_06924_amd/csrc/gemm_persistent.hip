@@ -14,7 +14,11 @@
 //    between them: while one tile's epilogue runs, the first K-tiles of the next are already
 //    landing in LDS (they need no registers), and the epilogue's stores retire while the next
 //    tile is multiplied.  A one-tile-per-workgroup launch pays launch, prologue latency and
-//    drain once per tile - four times per CU at 8192^3, since only one workgroup fits a CU.
+//    drain once per tile - four times per CU at 8192^3, since only one workgroup fits a CU;
+//  * the sixteen loads that a wave issues per K-tile are spread over two of its four steps.  The
+//    CU's vector-memory path takes a 1 KiB load about every 20 clocks, and a wave whose load
+//    cannot be accepted yet also holds back the MFMAs behind it: with all sixteen in the one step
+//    that follows the hand-over of the buffer, that step took 2.3 times as long as the others.
 #include <atomic>
 #include <mutex>
 #include <type_traits>
@@ -35,6 +39,9 @@ constexpr int kStage = 2 * kOperand;                // A tile then B tile
 constexpr int TM = 4, TN = 4;                       // 32x32 MFMA tiles per wave
 constexpr int kLdsScales = 2 * kStage;              // float[BM + BN]
 constexpr int kLdsBytes = kLdsScales + (BM + BN) * 4;
+// Loads of a K-tile issued in the last step of the K-tile that hands its buffer over (the step
+// that follows the barrier); the others go out in the first step of the next K-tile.
+constexpr int kLoadsLate = 8, kLoadsEarly = 16 - kLoadsLate;
 
 template <int MODE, bool SUMS, bool SCALE>
 __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int64_t N, int64_t K,
@@ -143,8 +150,8 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   advance();
   wait_loads();
   __syncthreads();
-  issue_loads(1);
-  advance();
+#pragma unroll
+  for (int i = 0; i < kLoadsLate; ++i) issue_load(1, i);   // the rest in the first step of K-tile 0
   fread(0, 0, 0);
 
   v16i acc[TM][TN];
@@ -184,9 +191,9 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       if (s == KS - 1) {
-        // K-tile g+1 (loads issued one whole K-tile ago) must have landed; after the barrier
-        // everybody is also done reading buffer `cur`, which takes K-tile g+2.  The 16 loads
-        // are issued one after each MFMA of this step, in program order.
+        // K-tile g+1 (its last loads went out three steps ago) must have landed; after the
+        // barrier everybody is also done reading buffer `cur`, which takes K-tile g+2: the
+        // first kLoadsLate of its loads go out here, evenly between the MFMAs of this step.
         wait_loads();
         __syncthreads();
         fread(cur ^ 1, 0, (s + 1) & 1);
@@ -196,7 +203,9 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
 #pragma unroll
           for (int b = 0; b < TN; ++b) {
             acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
-            issue_load(cur, a * TN + b);
+#pragma unroll
+            for (int n = 0; n < kLoadsLate; ++n)
+              if (((n + 1) * 16) / kLoadsLate - 1 == a * TN + b) issue_load(cur, n);
             __builtin_amdgcn_sched_barrier(0);
           }
         if (MODE == kGemmAccum && pf_on && kt >= pf0 && kt < pf0 + kPfTiles) {
@@ -216,6 +225,22 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
                 }
             }
         }
+      } else if (s == 0) {
+        // the remaining loads of K-tile g+1 (buffer cur ^ 1, handed over by the barrier of the
+        // step before), evenly between the MFMAs of this step; then the cursor moves on
+        fread(cur, s + 1, (s + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) {
+            acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
+#pragma unroll
+            for (int n = 0; n < kLoadsEarly; ++n)
+              if (((n + 1) * 16) / kLoadsEarly - 1 == a * TN + b) issue_load(cur ^ 1, kLoadsLate + n);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        advance();
       } else {
         fread(cur, s + 1, (s + 1) & 1);
 #pragma unroll
@@ -233,7 +258,6 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    advance();
   }
 
     // ================= epilogue of tile (tile_m, tile_n); no bounds checks: tiles are full
