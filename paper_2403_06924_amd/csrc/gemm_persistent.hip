@@ -15,10 +15,15 @@
 //    landing in LDS (they need no registers), and the epilogue's stores retire while the next
 //    tile is multiplied.  A one-tile-per-workgroup launch pays launch, prologue latency and
 //    drain once per tile - four times per CU at 8192^3, since only one workgroup fits a CU;
-//  * the sixteen loads that a wave issues per K-tile are spread over two of its four steps.  The
-//    CU's vector-memory path takes a 1 KiB load about every 20 clocks, and a wave whose load
-//    cannot be accepted yet also holds back the MFMAs behind it: with all sixteen in the one step
-//    that follows the hand-over of the buffer, that step took 2.3 times as long as the others.
+//  * LDS holds three buffers for the tiles of A and two for the tiles of B (5 x 32 KiB, all of a
+//    CU's LDS).  The sixteen loads that a wave issues per K-tile are spread evenly over its four
+//    steps: the CU's vector-memory path takes a 1 KiB load about every 20 clocks, and a wave
+//    whose load cannot be accepted yet also holds back the MFMAs behind it (with all sixteen in
+//    the one step that follows the hand-over of a buffer, that step took 2.3 times as long as
+//    the others).  The third A buffer is what makes room for that: the A tile of K-tile g+2 is
+//    fetched during the middle steps of K-tile g, one K-tile earlier than a two-buffer scheme
+//    could, so those loads also have twice as long to land, which matters when the operands
+//    come from HBM rather than from the caches.
 #include <atomic>
 #include <mutex>
 #include <type_traits>
@@ -35,13 +40,17 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 256, BN = 256, BK = 128, KS = BK / 32;
 constexpr int kOperand = BM * BK;                   // 32 KiB per operand tile
-constexpr int kStage = 2 * kOperand;                // A tile then B tile
 constexpr int TM = 4, TN = 4;                       // 32x32 MFMA tiles per wave
-constexpr int kLdsScales = 2 * kStage;              // float[BM + BN]
-constexpr int kLdsBytes = kLdsScales + (BM + BN) * 4;
-// Loads of a K-tile issued in the last step of the K-tile that hands its buffer over (the step
-// that follows the barrier); the others go out in the first step of the next K-tile.
-constexpr int kLoadsLate = 8, kLoadsEarly = 16 - kLoadsLate;
+constexpr int kABufs = 3, kBBufs = 2;               // LDS buffers of the A tiles and of the B tiles
+constexpr int kLdsB = kABufs * kOperand;            // the B buffers follow the A buffers
+constexpr int kLdsBytes = kLdsB + kBBufs * kOperand;   // 160 KiB; the epilogue's scales borrow a free A buffer
+constexpr int kLoads = 8;                           // loads per wave, operand and K-tile
+
+// all but the newest n vector-memory operations of this wave have completed
+template <int N>
+__device__ __forceinline__ void wait_loads_but() {
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
 
 template <int MODE, bool SUMS, bool SCALE>
 __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int64_t N, int64_t K,
@@ -51,8 +60,6 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
                                                                  GemmEpilogue ep, GemmSecond sec) {
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
   if (MODE == kGemmAccum && guard_tripped(ep)) return;   // the whole grid leaves together
-  float* sc_row = reinterpret_cast<float*>(lds + kLdsScales);
-  float* sc_col = sc_row + BM;
   // LDS byte address of the first stage (an address-space-3 pointer is a 32-bit offset)
   const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) int8_t*)lds);
 
@@ -72,8 +79,10 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   // (l%8) ^ ((row >> 1) & 7); (row >> 1) & 7 = ((l >> 4) + 4j) & 7 depends on j only through
   // its parity.
   const int lrow = lane >> 3;
-  int64_t vba = blockIdx.x, kta = 0;                // cursor of the K-tile being fetched
+  int64_t vba = blockIdx.x;                         // cursor of the K-tile being fetched: output tile,
+  int kta = 0;                                      // ... K-tile within it
   int proda = p_lo;                                 // ... and the product it belongs to
+  const int nk32 = (int)nk;
   const int8_t *pa, *pb;                            // row 64w of that K-tile in A and in B
   int64_t cur_lda = lda, cur_ldb = ldb;
   int64_t goff_a0 = 0, goff_a1 = 0, goff_b0 = 0, goff_b1 = 0;
@@ -88,14 +97,15 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
     goff_a1 = (int64_t)lrow * cur_lda + 16 * ((lane & 7) ^ (((lane >> 4) + 4) & 7));
     goff_b0 = (int64_t)lrow * cur_ldb + 16 * ((lane & 7) ^ ((lane >> 4) & 7));
     goff_b1 = (int64_t)lrow * cur_ldb + 16 * ((lane & 7) ^ (((lane >> 4) + 4) & 7));
-    pa = A0 + (tm * BM + 64 * w) * cur_lda + kta * BK;
-    pb = B0 + (tn * BN + 64 * w) * cur_ldb + kta * BK;
+    pa = A0 + (tm * BM + 64 * w) * cur_lda + (int64_t)kta * BK;
+    pb = B0 + (tn * BN + 64 * w) * cur_ldb + (int64_t)kta * BK;
   };
+  int kstep = BK;                                   // 0 once the cursor has reached the end of the launch
   auto advance = [&]() {
-    if (kta + 1 < nk) {
-      ++kta;
-      pa += BK;
-      pb += BK;
+    if (kta + 1 < nk32) {
+      kta += kstep ? 1 : 0;
+      pa += kstep;
+      pb += kstep;
     } else if (proda < p_hi) {
       ++proda;
       kta = 0;
@@ -105,34 +115,40 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
       proda = p_lo;
       kta = 0;
       point();
-    }                                               // else stay on the last K-tile (harmless re-fetch)
+    } else {
+      kstep = 0;                                    // stay on the last K-tile (harmless re-fetch)
+    }
   };
-  // load i (0..15) of the K-tile at the cursor into LDS buffer `stage`: even i -> A, odd i -> B
-  auto issue_load = [&](int stage, int i) {
+  // The same where the caller knows that the cursor stays inside its output tile (or has reached
+  // the end): no branch, and so no point where the compiler, having seen the reloads of spilled
+  // registers on the other path, would wait for every load in flight.
+  auto advance_within = [&]() {
+    kta += kstep ? 1 : 0;
+    pa += kstep;
+    pb += kstep;
+  };
+  // load j (0..7) of the A resp. B tile at the cursor into buffer `buf` of that operand
+  auto issue_a = [&](int buf, int j) {
     // wave-uniform by construction; readfirstlane tells the compiler so (it feeds M0)
-    const uint32_t la = __builtin_amdgcn_readfirstlane(lds0 + stage * kStage + (64 * w) * BK);
-    const int j = i >> 1;
-    if (i & 1)
-      load_to_lds(pb + (int64_t)(8 * j) * cur_ldb + ((j & 1) ? goff_b1 : goff_b0), la + kOperand + j * 8 * BK);
-    else
-      load_to_lds(pa + (int64_t)(8 * j) * cur_lda + ((j & 1) ? goff_a1 : goff_a0), la + j * 8 * BK);
+    const uint32_t la = __builtin_amdgcn_readfirstlane(lds0 + buf * kOperand + (64 * w) * BK);
+    load_to_lds(pa + (int64_t)(8 * j) * cur_lda + ((j & 1) ? goff_a1 : goff_a0), la + j * 8 * BK);
   };
-  auto issue_loads = [&](int stage) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) issue_load(stage, i);
+  auto issue_b = [&](int buf, int j) {
+    const uint32_t la = __builtin_amdgcn_readfirstlane(lds0 + kLdsB + buf * kOperand + (64 * w) * BK);
+    load_to_lds(pb + (int64_t)(8 * j) * cur_ldb + ((j & 1) ? goff_b1 : goff_b0), la + j * 8 * BK);
   };
 
   // ---- fragment reads: lane (frow, kh) reads logical piece 2*step + kh of its rows
   const int frow = lane & 31, kh = lane >> 5, key = (frow >> 1) & 7;
   const int a_row = (wm * (BM / 2) + frow) * BK;
-  const int b_row = kOperand + (wn * (BN / 2) + frow) * BK;
+  const int b_row = kLdsB + (wn * (BN / 2) + frow) * BK;
   int xoff[KS];
 #pragma unroll
   for (int s = 0; s < KS; ++s) xoff[s] = 16 * ((2 * s + kh) ^ key);
   v4i fa[2][TM], fb[2][TN];
-  auto fread = [&](int stage, int step, int slot) {
-    const int8_t* As = lds + stage * kStage + a_row + xoff[step];
-    const int8_t* Bs = lds + stage * kStage + b_row + xoff[step];
+  auto fread = [&](int abuf, int bbuf, int step, int slot) {
+    const int8_t* As = lds + abuf * kOperand + a_row + xoff[step];
+    const int8_t* Bs = lds + bbuf * kOperand + b_row + xoff[step];
 #pragma unroll
     for (int t = 0; t < TM; ++t) fa[slot][t] = *reinterpret_cast<const v4i*>(As + t * 32 * BK);
 #pragma unroll
@@ -145,14 +161,20 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   float sreg_row = (p_lo ? sec.s_row : ep.s_row)[tile_m * BM + tid];
   float sreg_col = (p_lo ? sec.s_col : ep.s_col)[tile_n * BN + tid];
 
+  // K-tile 0, the A tile of K-tile 1 and the first half of its B tile
   point();
-  issue_loads(0);
-  advance();
-  wait_loads();
-  __syncthreads();
 #pragma unroll
-  for (int i = 0; i < kLoadsLate; ++i) issue_load(1, i);   // the rest in the first step of K-tile 0
-  fread(0, 0, 0);
+  for (int j = 0; j < kLoads; ++j) issue_a(0, j);
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) issue_b(0, j);
+  advance();
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) issue_a(1, j);
+#pragma unroll
+  for (int j = 0; j < kLoads / 2; ++j) issue_b(1, j);
+  wait_loads_but<kLoads + kLoads / 2>();            // K-tile 0 has landed
+  __syncthreads();
+  fread(0, 0, 0, 0);
 
   v16i acc[TM][TN];
 #pragma unroll
@@ -165,12 +187,13 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   // Accumulate mode reads the tile of C it adds to.  Every compute unit reaches its epilogue at
   // about the same time, so loads issued there arrive as one burst per round while the memory
   // system idles in between: the first band of the tile (the lane's 16 rows x TN columns of the
-  // first 32 rows of its wave tile) is therefore fetched during the K loop instead, a slice per
-  // K-tile over the kPfTiles K-tiles before the last one, and waits in registers.
+  // first 32 rows of its wave tile) is therefore fetched during the K loop instead, a few K-tiles
+  // before the last one, and waits in registers.  All its loads go out in one K-tile and straight
+  // into their registers: nothing in the K loop reads a register that a load is still to fill
+  // (the compiler, which does not see the operand loads, would wait there for all of them).
   constexpr int kPfBands = 1;                       // bands fetched ahead (of TM); two cost more in spills than they hide
-  constexpr int kPfTiles = 8 * kPfBands;            // 16 rows x TN values per band = 8 slices of 2 rows
-  const bool pf_on = MODE == kGemmAccum && !SCALE && nk > kPfTiles;   // (alpha / beta need the registers)
-  const int64_t pf0 = nk - 1 - kPfTiles;            // K-tile that issues slice 0
+  const bool pf_on = MODE == kGemmAccum && !SCALE && nk >= 8;   // (alpha / beta need the registers)
+  const int64_t pf0 = nk - 4;                       // K-tile that issues the loads
   float pre[kPfBands][TN][16];
 #pragma unroll
   for (int a = 0; a < kPfBands; ++a)
@@ -182,85 +205,93 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   const int cbase = wn * (BN / 2) + cl;
 
   const int64_t my_tiles = (total - blockIdx.x + G - 1) / G;
-  int g = 0;                                        // parity of the K-tile stream across tiles
+  int g = 0;                                        // position in the K-tile stream across tiles
+  int abuf = 0;                                     // A buffer of K-tile g (g mod 3)
   int prod = p_lo;                                  // product being multiplied (pairs: 0, 1, 0, 1, ...)
   const bool two = p_lo != p_hi;
   for (int64_t tile = 0; tile < my_tiles * (p_hi - p_lo + 1); ++tile) {
-  for (int64_t kt = 0; kt < nk; ++kt, ++g) {
-    const int cur = g & 1;
+  auto ktile = [&](int64_t kt, auto crossing) {
+    // Loads of this K-tile's four steps, one after every fourth MFMA:
+    //   step 0: second half of the B tile of K-tile g+1 (its buffer was handed over by the
+    //           barrier of the step before); then the cursor moves on to K-tile g+2;
+    //   steps 1, 2: the A tile of K-tile g+2, into the buffer that K-tile g-1 left;
+    //   step 3, after the barrier: first half of the B tile of K-tile g+2, into this K-tile's.
+    const int bbuf = g & 1;
+    const int anext = abuf == kABufs - 1 ? 0 : abuf + 1, aload = anext == kABufs - 1 ? 0 : anext + 1;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       if (s == KS - 1) {
-        // K-tile g+1 (its last loads went out three steps ago) must have landed; after the
-        // barrier everybody is also done reading buffer `cur`, which takes K-tile g+2: the
-        // first kLoadsLate of its loads go out here, evenly between the MFMAs of this step.
-        wait_loads();
+        // K-tile g+1 must have landed: everything but the eight loads of the A tile of K-tile
+        // g+2.  After the barrier everybody is also done reading this K-tile's buffers.
+        wait_loads_but<kLoads>();
         __syncthreads();
-        fread(cur ^ 1, 0, (s + 1) & 1);
+        fread(anext, bbuf ^ 1, 0, (s + 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
           for (int b = 0; b < TN; ++b) {
             acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
-#pragma unroll
-            for (int n = 0; n < kLoadsLate; ++n)
-              if (((n + 1) * 16) / kLoadsLate - 1 == a * TN + b) issue_load(cur, n);
+            if (b == TN - 1) issue_b(bbuf, a);
             __builtin_amdgcn_sched_barrier(0);
           }
-        if (MODE == kGemmAccum && pf_on && kt >= pf0 && kt < pf0 + kPfTiles) {
-          // slice kt - pf0 of the first band of C: rows 8 (s >> 1) + 2 (s & 1) + {0, 1} of the band
+        if (MODE == kGemmAccum && pf_on && kt == pf0) {
+          // the first band of C: rows 8 (v >> 2) + (v & 3) of the lane's 32-row band
           const float* cband0 = ep.C + (tile_m * BM + wm * (BM / 2) + 4 * half) * ep.ldc + tile_n * BN + cbase;
-          const bool cached = p_lo != p_hi && prod == 1;
+          if (p_lo != p_hi && prod == 1) {            // the first product of the pair left the tile in the caches
 #pragma unroll
-          for (int sl = 0; sl < kPfTiles; ++sl)
-            if (kt - pf0 == sl) {
+            for (int v = 0; v < 16; ++v)
 #pragma unroll
-              for (int vv = 0; vv < 2; ++vv)
+              for (int b = 0; b < TN; ++b) pre[0][b][v] = cband0[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32];
+          } else {
 #pragma unroll
-                for (int b = 0; b < TN; ++b) {
-                  const int a = sl >> 3, v = 2 * (sl & 7) + vv;
-                  const float* src = &cband0[(int64_t)(a * 32 + 8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32];
-                  pre[a][b][v] = cached ? *src : __builtin_nontemporal_load(src);
-                }
-            }
+            for (int v = 0; v < 16; ++v)
+#pragma unroll
+              for (int b = 0; b < TN; ++b)
+                pre[0][b][v] = __builtin_nontemporal_load(&cband0[(int64_t)(8 * (v >> 2) + (v & 3)) * ep.ldc + b * 32]);
+          }
         }
-      } else if (s == 0) {
-        // the remaining loads of K-tile g+1 (buffer cur ^ 1, handed over by the barrier of the
-        // step before), evenly between the MFMAs of this step; then the cursor moves on
-        fread(cur, s + 1, (s + 1) & 1);
+      } else {
+        fread(abuf, bbuf, s + 1, (s + 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
           for (int b = 0; b < TN; ++b) {
             acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
-#pragma unroll
-            for (int n = 0; n < kLoadsEarly; ++n)
-              if (((n + 1) * 16) / kLoadsEarly - 1 == a * TN + b) issue_load(cur ^ 1, kLoadsLate + n);
+            if (b == TN - 1) {
+              if (s == 0) issue_b(bbuf ^ 1, kLoads / 2 + a);
+              if (s == 1) issue_a(aload, a);
+              if (s == 2) issue_a(aload, kLoads / 2 + a);
+            }
             __builtin_amdgcn_sched_barrier(0);
           }
-        advance();
-      } else {
-        fread(cur, s + 1, (s + 1) & 1);
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b)
-            acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
-        // issue order: one fragment read after each of the first eight MFMAs (0x008 MFMA, 0x100 DS read)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (s == 0) {
+          if (decltype(crossing)::value) advance();
+          else advance_within();
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    abuf = anext;
+    ++g;
+  };
+  // The cursor is two K-tiles ahead and moves on in the first step of a K-tile: it leaves its
+  // output tile (or product) in K-tile nk - 2 and nowhere else.
+  if (nk >= 3) {
+    for (int64_t kt = 0; kt < nk - 2; ++kt) ktile(kt, std::false_type());
+    ktile(nk - 2, std::true_type());
+    ktile(nk - 1, std::false_type());
+  } else {
+    for (int64_t kt = 0; kt < nk; ++kt) ktile(kt, std::true_type());
   }
 
     // ================= epilogue of tile (tile_m, tile_n); no bounds checks: tiles are full
+    // The scales are staged in the A buffer that the last K-tile has just left (everybody passed
+    // that K-tile's barrier after its last read); the next loads into it go out in the second
+    // step of the next K-tile, which the barrier at the end of the epilogue holds back.
+    float* sc_row = reinterpret_cast<float*>(lds + (abuf == 0 ? kABufs - 1 : abuf - 1) * kOperand);
+    float* sc_col = sc_row + BM;
     sc_row[tid] = sreg_row;
     sc_col[tid] = sreg_col;
     __syncthreads();
@@ -374,6 +405,9 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
         if (half == 0) ep.col_part[(2 * tile_m + wm) * (ep.part_ld_n ? ep.part_ld_n : N) + n0 + cbase + b * 32] = c;
       }
     }
+    // everybody has read its scales: the A buffer that held them may be loaded again (a bare
+    // barrier: the stores of C stay in flight)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory");
     // next product of this tile, or the next output tile of this workgroup
     if (prod < p_hi) {
       prod = 1;
