@@ -155,6 +155,14 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
     for (int t = 0; t < TN; ++t) fb[slot][t] = *reinterpret_cast<const v4i*>(Bs + t * 32 * BK);
   };
 
+  // read r of a step's eight fragment reads: 0..3 -> A tiles, 4..7 -> B tiles
+  auto fread1 = [&](int abuf, int bbuf, int step, int slot, int r) {
+    if (r < TM)
+      fa[slot][r] = *reinterpret_cast<const v4i*>(lds + abuf * kOperand + a_row + xoff[step] + r * 32 * BK);
+    else
+      fb[slot][r - TM] = *reinterpret_cast<const v4i*>(lds + bbuf * kOperand + b_row + xoff[step] + (r - TM) * 32 * BK);
+  };
+
   // ---- the output tile being multiplied
   int64_t vb = blockIdx.x, tile_m, tile_n;
   tile_of(vb, tiles_m, tiles_n, tile_m, tile_n);
@@ -211,7 +219,7 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
   const bool two = p_lo != p_hi;
   for (int64_t tile = 0; tile < my_tiles * (p_hi - p_lo + 1); ++tile) {
   auto ktile = [&](int64_t kt, auto crossing) {
-    // Loads of this K-tile's four steps, one after every fourth MFMA:
+    // Loads of this K-tile's four steps, four in each:
     //   step 0: second half of the B tile of K-tile g+1 (its buffer was handed over by the
     //           barrier of the step before); then the cursor moves on to K-tile g+2;
     //   steps 1, 2: the A tile of K-tile g+2, into the buffer that K-tile g-1 left;
@@ -252,17 +260,20 @@ __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int6
           }
         }
       } else {
-        fread(abuf, bbuf, s + 1, (s + 1) & 1);
+        // the fragments of the next step: one read after each of the first eight MFMAs
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
           for (int b = 0; b < TN; ++b) {
             acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
-            if (b == TN - 1) {
-              if (s == 0) issue_b(bbuf ^ 1, kLoads / 2 + a);
-              if (s == 1) issue_a(aload, a);
-              if (s == 2) issue_a(aload, kLoads / 2 + a);
+            if (a * TN + b < 8) fread1(abuf, bbuf, s + 1, (s + 1) & 1, a * TN + b);
+            // ... and one load after every second MFMA of the other eight
+            if (a * TN + b >= 8 && !(b & 1)) {
+              const int n = (a * TN + b - 8) >> 1;
+              if (s == 0) issue_b(bbuf ^ 1, kLoads / 2 + n);
+              if (s == 1) issue_a(aload, n);
+              if (s == 2) issue_a(aload, kLoads / 2 + n);
             }
             __builtin_amdgcn_sched_barrier(0);
           }
