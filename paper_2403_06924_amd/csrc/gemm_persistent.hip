@@ -2,7 +2,7 @@
 // multiple of 128, 16-byte aligned operands): the shape of every large workload.
 //
 // Same output tile as gemm_i8_kernel (256 x 256 per 4-wave workgroup, 128 x 128 per wave,
-// v_mfma_i32_32x32x32_i8) with two differences made for gfx950:
+// v_mfma_i32_32x32x32_i8) with three differences made for gfx950:
 //
 //  * operand tiles go from global memory straight into LDS (global_load_lds_dwordx4): no
 //    staging registers and no ds_write instructions.  The hardware writes the 64 lanes of one
