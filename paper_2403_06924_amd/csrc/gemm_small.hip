@@ -127,6 +127,14 @@ __global__ __launch_bounds__(256) void gemm_i8_small_kernel(int64_t M, int64_t N
     for (int t = 0; t < TN; ++t) fb[slot][t] = *reinterpret_cast<const v4i*>(Bs + t * 32 * BK);
   };
 
+  // read r of a step's four fragment reads: 0, 1 -> A tiles, 2, 3 -> B tiles
+  auto fread1 = [&](int stage, int step, int slot, int r) {
+    if (r < TM)
+      fa[slot][r] = *reinterpret_cast<const v4i*>(lds + stage * kStage + a_row + xoff[step] + r * 32 * BK);
+    else
+      fb[slot][r - TM] = *reinterpret_cast<const v4i*>(lds + stage * kStage + b_row + xoff[step] + (r - TM) * 32 * BK);
+  };
+
   // scales of the tile: threads 0..127 hold the row scales, 128..255 the column scales
   float sreg = tid < BM ? (p_lo ? sec.s_row : ep.s_row)[m0 + tid] : (p_lo ? sec.s_col : ep.s_col)[n0 + tid - BM];
 
@@ -156,37 +164,26 @@ __global__ __launch_bounds__(256) void gemm_i8_small_kernel(int64_t M, int64_t N
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
         if (s == KS - 1) {
-          // K-tile g+1 must have landed: everything but the eight loads of K-tile g+2.  After the
-          // barrier everybody is also done reading the stage of K-tile g-1, which takes K-tile
-          // g+3; its loads are issued two after each MFMA of this step.
-          wait_loads_but<kLoadsPerTile>();
+          // K-tile g+1 must have landed: everything but the eight loads of K-tile g+2 and the
+          // six of K-tile g+3 that this K-tile's earlier steps issued.
+          wait_loads_but<2 * kLoadsPerTile - 2>();
           __syncthreads();
           fread((cur + 1) & (NST - 1), 0, (s + 1) & 1);
           __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int a = 0; a < TM; ++a)
-#pragma unroll
-            for (int b = 0; b < TN; ++b) {
-              acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
-              issue_load((cur + 3) & (NST - 1), 2 * (a * TN + b));
-              issue_load((cur + 3) & (NST - 1), 2 * (a * TN + b) + 1);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-        } else {
-          fread(cur, s + 1, (s + 1) & 1);
-#pragma unroll
-          for (int a = 0; a < TM; ++a)
-#pragma unroll
-            for (int b = 0; b < TN; ++b)
-              acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
-          // issue order: one fragment read after each MFMA (0x008 MFMA, 0x100 DS read)
-#pragma unroll
-          for (int i = 0; i < TM + TN; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          }
         }
-        __builtin_amdgcn_sched_barrier(0);
+        // The stage of K-tile g-1 was handed over by the barrier of that K-tile and takes K-tile
+        // g+3: two of its eight loads go out in each step (the CU's vector-memory path takes a
+        // 1 KiB load about every 20 clocks; a wave whose load is not accepted yet also holds back
+        // the MFMAs behind it).  The fragments of the next step: one read after each MFMA.
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b) {
+            acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[s & 1][a], fb[s & 1][b], acc[a][b], 0, 0, 0);
+            if (s != KS - 1) fread1(cur, s + 1, (s + 1) & 1, a * TN + b);
+            if (b == TN - 1) issue_load((cur + 3) & (NST - 1), 2 * s + a);
+            __builtin_amdgcn_sched_barrier(0);
+          }
       }
       advance();
     }
