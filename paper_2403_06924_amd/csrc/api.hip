@@ -50,10 +50,12 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // Densities at and above which SRQ_STRATEGY_AUTO runs a sparse product on the matrix cores
 // (the paper's switch between SPMM and GEMM, Algorithm 1 lines 11-15, with the ratio of the
 // two kernels' throughputs on MI355X in place of the paper's eta).  Measured at 8192^3: the
-// vector-ALU kernel takes 0.19 ms + 0.30 ms per percent of density for A' (rows of C written
-// straight), 0.15 ms + 0.37 ms per percent for B' (columns of C, through LDS); the expanded
-// operand on the matrix cores takes 0.49-0.58 ms at any density.  The same crossovers (1.3-1.5 %
-// and 0.75 %) were measured at 2048^3 and 4096^3.
+// vector-ALU kernel takes 0.19 ms + 0.37 ms per percent of density for A' (rows of C written
+// straight), 0.15 ms + 0.54 ms per percent for B' (columns of C, through LDS); the expanded
+// operand on the matrix cores takes 0.48 ms at any density when both terms share a launch, 0.51
+// alone.  Whole calls with both terms on one or the other kernel break even at 0.65 % (8192^3),
+// 0.6 % (4096^3), 0.95 % (6144^3, whose 576 tiles load the 256 compute units unevenly) and
+// 0.62 % (16384^3).
 // execution of a correction term as reported in srq_stats_t (0: term skipped)
 constexpr int kPathValu = 1, kPathMfma = 2, kPathDense = 3, kPath24 = 4, kPathColblock = 5;
 constexpr int kPathOnDevice = 6;          // host-side marker: vector ALUs or matrix cores, decided on the device
@@ -72,10 +74,10 @@ constexpr double kColblockKeepRatio = 0.9;
 
 constexpr int64_t kNoCap = INT64_MAX;     // capacity of an operand that is not compacted
 
-constexpr double kAutoMfmaDensityA = 0.012;
-constexpr double kAutoMfmaDensityALongK = 0.008;
-constexpr double kAutoMfmaDensityB = 0.009;
-constexpr double kAutoMfmaDensityBLongK = 0.0075;
+constexpr double kAutoMfmaDensityA = 0.008;
+constexpr double kAutoMfmaDensityALongK = 0.0062;
+constexpr double kAutoMfmaDensityB = 0.007;
+constexpr double kAutoMfmaDensityBLongK = 0.0062;
 
 struct Carver {
   char* base;
@@ -924,7 +926,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
     // on the device, by the scan kernel itself where it scans both operands (it then also writes
     // the statistics), else by a kernel of its own.
     // (for K > 8192 the K x 512-byte slab of codes an XCD gathers from outgrows its L2 and the
-    // vector-ALU kernel loses earlier: measured crossover 0.8 % at 16384^3)
+    // vector-ALU kernel loses earlier: measured crossover 0.62 % at 16384^3)
     const int64_t min_mfma_a =
         (int64_t)ceil((K > 8192 ? kAutoMfmaDensityALongK : kAutoMfmaDensityA) * (double)M * (double)K);
     const int64_t min_mfma_b =
@@ -955,7 +957,7 @@ srq_status_t srq_compensated_gemm(srq_handle_t h, int64_t M, int64_t N, int64_t 
         return strategy_path(strategy);
       };
       // (for K > 8192 the K x 512-byte slab of codes an XCD gathers from outgrows its L2 and the
-      // vector-ALU kernel loses earlier: measured crossover 0.8 % at 16384^3)
+      // vector-ALU kernel loses earlier: measured crossover 0.62 % at 16384^3)
       if (term_a) path_a = pick(da, K > 8192 ? kAutoMfmaDensityALongK : kAutoMfmaDensityA);
       if (term_b) path_b = pick(db, K > 8192 ? kAutoMfmaDensityBLongK : kAutoMfmaDensityB);
       if (term_a && strategy == SRQ_STRATEGY_AUTO) h->last_path_a = path_a;
