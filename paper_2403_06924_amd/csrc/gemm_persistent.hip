@@ -46,12 +46,6 @@ constexpr int kLdsB = kABufs * kOperand;            // the B buffers follow the 
 constexpr int kLdsBytes = kLdsB + kBBufs * kOperand;   // 160 KiB; the epilogue's scales borrow a free A buffer
 constexpr int kLoads = 8;                           // loads per wave, operand and K-tile
 
-// all but the newest n vector-memory operations of this wave have completed
-template <int N>
-__device__ __forceinline__ void wait_loads_but() {
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
 template <int MODE, bool SUMS, bool SCALE>
 __global__ __launch_bounds__(256) void gemm_i8_persistent_kernel(int64_t M, int64_t N, int64_t K,
                                                                  const int8_t* __restrict__ Qa, int64_t lda,

@@ -32,12 +32,6 @@ constexpr int kLdsColX = kLdsRowX + 2 * BM * 4;        // double[2][BN]: column 
 constexpr int kLdsBytes = kLdsColX + 2 * BN * 8;
 constexpr int kLoadsPerTile = 8;                    // per wave and K-tile: 4 for A, 4 for B
 
-// all but the newest n vector-memory operations of this wave have completed
-template <int N>
-__device__ __forceinline__ void wait_loads_but() {
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
 template <int MODE, bool SUMS, bool SCALE>
 __global__ __launch_bounds__(256) void gemm_i8_small_kernel(int64_t M, int64_t N, int64_t K,
                                                             const int8_t* __restrict__ Qa, int64_t lda,

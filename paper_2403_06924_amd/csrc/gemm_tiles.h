@@ -26,6 +26,13 @@ static __device__ __forceinline__ void load_to_lds(const int8_t* gptr, uint32_t 
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
 }
 static __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+// All but the newest N vector-memory operations of this wave have completed.  (Loads complete in
+// the order they were issued; stores may overtake them, so a count is only relied on where the
+// loads to be waited for are older than N younger LOADS.)
+template <int N>
+static __device__ __forceinline__ void wait_loads_but() {
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
 
 }  // namespace srq
 
