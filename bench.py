@@ -140,6 +140,12 @@ def stage_bench(args, b, torch, h, w, Ad, Bd, sa, sb, drow, dcol, theta_a, theta
             # box to box, so the two are timed in alternating blocks inside one warm sequence
             Ci = torch.empty((M, N), dtype=torch.int32, device="cuda")
             QbT = Qb.t()                              # the library takes B as K x N; this view is column-major
+            try:
+                torch._int_mm(Qa, QbT, out=Ci)
+            except Exception as ex:                   # no INT8 GEMM in this torch build / for this shape
+                line["library_int_mm"] = {"value": None, "note": "torch._int_mm failed: %r" % (ex,)}
+                print(json.dumps(line))
+                return
             blocks, per = 6, max(1, args.steps // 6)
             t_own, t_lib = [], []
             for blk in range(blocks + 1):
