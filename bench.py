@@ -262,7 +262,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    h.profile_enable(True)
+    # Inside the timed region the library times the three products only (the launches of the
+    # roofline below): every event record costs a call about 3 us, because the kernel after it
+    # cannot start under the tail of the kernel before it.  The other stages are timed over a few
+    # further calls after the region.
+    product_stages = ("gemm", "term1", "term2")
+    h.profile_enable(True, products_only=True)
     stage_ms = {k: 0.0 for k in b.STAGES}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -273,9 +278,16 @@ def main():
                 stage_ms[k] += v
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    h.profile_enable(False)
     ms_per_step = dt / args.steps * 1e3
     stage_ms = {k: v / args.steps for k, v in stage_ms.items()}
+    extra = min(args.steps, 20)
+    h.profile_enable(True)
+    for _ in range(extra):
+        step()
+    for k, v in h.profile_read().items():
+        if k not in product_stages:
+            stage_ms[k] = v / extra
+    h.profile_enable(False)
     graph_replay = None
     recordable = args.dense_fallback > 1.0 or args.dense_fallback <= 0.0
     if recordable and not args.eager:
@@ -432,6 +444,8 @@ def main():
         "density_a": st["nnz_a"] / (M * K), "density_b": st["nnz_b"] / (N * K),
         "path_a": st["path_a"], "path_b": st["path_b"],
         "stage_ms": stage_ms,
+        "stage_ms_source": "gemm, term1, term2: HIP events around the launches inside the timed region; the other "
+                           "stages: the same events over %d further calls after it" % min(args.steps, 20),
         "graph_replay": graph_replay,
         "variants": variants,
         "roofline": roof,

@@ -169,7 +169,12 @@ srq_status_t srq_set_auto_hint(srq_handle_t handle, int path_a, int path_b);
  * milliseconds per stage, summed over the calls made since the previous read (or since
  * enabling): read after every call for the times of that call, or after a run of calls issued
  * back to back for their totals without a wait in between.  The events of the last 64 calls
- * are kept; earlier ones are forgotten.  0 for a stage that did not run. */
+ * are kept; earlier ones are forgotten.  0 for a stage that did not run.
+ * `enable`: 0 = off, SRQ_PROFILE_ALL = every stage, SRQ_PROFILE_PRODUCTS = only the three
+ * products (SRQ_STAGE_GEMM, SRQ_STAGE_TERM1, SRQ_STAGE_TERM2; the other entries read 0): an event
+ * record costs the call about 3 microseconds, since the kernel after it cannot start under the
+ * tail of the kernel before it. */
+enum { SRQ_PROFILE_ALL = 1, SRQ_PROFILE_PRODUCTS = 2 };
 enum {
   SRQ_STAGE_QUANTIZE = 0,   /* amax, scales, codes of A and B, max |residual|             */
   SRQ_STAGE_GEMM = 1,       /* INT8 product, dequantization, partial sums of |D_F|        */

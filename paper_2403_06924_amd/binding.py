@@ -21,6 +21,7 @@ LAYOUT_VECTOR_MAJOR, LAYOUT_ELEMENT_MAJOR = 0, 1
 ROUND_NEAREST_EVEN, ROUND_TRUNC = 0, 1
 STRATEGY_AUTO, STRATEGY_CSR_VALU, STRATEGY_CSR_MFMA, STRATEGY_CSR_SMFMAC, STRATEGY_COLBLOCK = 0, 1, 2, 3, 4
 SCALE_VECTOR, SCALE_GLOBAL = 0, 1
+PROFILE_ALL, PROFILE_PRODUCTS = 1, 2
 
 EXPORTS = [
     "srq_create", "srq_destroy", "srq_workspace_bytes", "srq_set_workspace",
@@ -192,8 +193,11 @@ class Srq:
         STRATEGY_AUTO to pick for term 1 / term 2 in the following calls."""
         self._ret(self.lib.srq_set_auto_hint(self.h, int(path_a), int(path_b)), "srq_set_auto_hint")
 
-    def profile_enable(self, on=True):
-        self._ret(self.lib.srq_profile_enable(self.h, 1 if on else 0), "srq_profile_enable")
+    def profile_enable(self, on=True, products_only=False):
+        """Stage timers on (every stage, or only the three products: fewer event records in the
+        call) or off."""
+        level = 0 if not on else (PROFILE_PRODUCTS if products_only else PROFILE_ALL)
+        self._ret(self.lib.srq_profile_enable(self.h, level), "srq_profile_enable")
 
     def profile_read(self):
         """Milliseconds per stage, summed over the compensated_gemm calls since the previous read

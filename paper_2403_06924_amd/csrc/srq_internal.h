@@ -15,6 +15,7 @@ struct srq_context {
   int64_t* host_nnz;     // pinned host buffer for the two counters read back in synchronising modes
   srq_intermediates_t last;
   int prof_enabled;
+  unsigned prof_mask;                       // bit i: stage i is timed
   // stage events of the last kProfRing calls (slot = call number mod kProfRing)
   unsigned prof_used[64];                   // bit i: stage i ran in that call
   hipEvent_t prof_ev[64][2 * SRQ_NUM_STAGES];   // start/stop per stage, created on enable

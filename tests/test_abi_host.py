@@ -210,5 +210,6 @@ def test_handle_settings_validation(dry):
     assert lib.srq_profile_read(h, ms) == b.OK and all(x == 0.0 for x in ms)   # nothing recorded: zeros
     assert lib.srq_profile_read(h, None) == b.INVALID_ARG
     assert lib.srq_profile_enable(h, 1) == b.NO_DEVICE            # events need a device
+    assert lib.srq_profile_enable(h, b.PROFILE_PRODUCTS) == b.NO_DEVICE
     assert lib.srq_profile_enable(h, 0) == b.OK
 

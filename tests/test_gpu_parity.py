@@ -598,6 +598,29 @@ def test_stage_timers_sum_over_calls(srq, b):
         srq.profile_enable(False)
 
 
+def test_stage_timers_products_only(srq, b):
+    """SRQ_PROFILE_PRODUCTS times the three products and nothing else (fewer event records in
+    the call); the result of the call is the same with the timers at either level or off."""
+    A, B = wl.make_inputs("C2", 256, 256, 256)
+    Ad, Bd = dev(A), dev(B)
+    C0, _, _ = srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
+    srq.profile_enable(True, products_only=True)
+    try:
+        for _ in range(3):
+            C1, _, _ = srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
+        ms = srq.profile_read()
+        assert ms["gemm"] > 0 and ms["term1"] > 0
+        assert all(ms[k] == 0.0 for k in ("quantize", "select", "residual", "term1_prep", "term2_prep"))
+        assert (host(C1) == host(C0)).all()
+        srq.profile_enable(True)                                            # back to every stage
+        C2, _, _ = srq.compensated_gemm(Ad, Bd, 0.5, 0.5, strategy=b.STRATEGY_CSR_MFMA)
+        ms = srq.profile_read()
+        assert ms["quantize"] > 0 and ms["select"] > 0 and ms["gemm"] > 0
+        assert (host(C2) == host(C0)).all()
+    finally:
+        srq.profile_enable(False)
+
+
 def test_run_twice_is_deterministic(srq, b):
     A, B = wl.make_inputs("C3", 300, 260, 512)
     Ad, Bd = dev(A), dev(B)
